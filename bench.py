@@ -1,0 +1,158 @@
+"""Benchmark of the TAH-Quant codec hot path on one MI355X.
+
+One step = tahq_encode + tahq_decode of one micro-batch of synthetic activations that is
+already resident in HBM.  Prints ONE JSON line: encode+decode GB/s of input activations, the
+roofline of the dominant kernel (measured live with events on the launch stream) and the CPU
+oracle's throughput on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def algorithmic_bytes(w, packed_size, T, select):
+    """Bytes each kernel must move per launch (per-element figures x elements of one launch)."""
+    n, e = w.elements, w.bytes_per_element
+    meta = packed_size - (w.tile // 8) * 3 * T            # rough: everything that is not 3-bit payload
+    del meta
+    return {
+        # entropy kernel: reads the tensor once, writes one float per tile
+        "k_entropy": n * e + 4 * T,
+        # quantize+pack kernel: reads the tensor once, reads bit map + ranks, writes the stream
+        "k_quant_pack": n * e + packed_size,
+        # decode kernel: reads the stream once, writes the tensor once
+        "k_decode": packed_size + n * e,
+    }
+
+
+def cpu_baseline(index, w):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    import workloads
+    from oracle import o32
+    batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
+    ws, x = workloads.generate(index, batch=batch)
+    ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, ws.tile, ws.dtype, ws.budget_bits)
+    t0 = time.perf_counter()
+    packed = o32.encode(ocfg, x)
+    t1 = time.perf_counter()
+    o32.decode(ocfg, packed, ws.dtype)
+    t2 = time.perf_counter()
+    nbytes = ws.elements * ws.bytes_per_element
+    return {
+        "value": nbytes / (t2 - t0) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {batch} of {w.batch} samples of {w.name} ({ws.elements} elements): "
+                  f"encode {t1 - t0:.2f} s + decode {t2 - t1:.2f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (default: the metric's config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this codec runs on one GPU; nothing here shards across GPUs (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    import paper_2506_01352_amd as tahq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    tahq.binding._load()
+
+    w, x = workloads.generate(args.config)
+    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
+    d_in = torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+    del x
+    codec = tahq.Codec(cfg, device="cuda:0")          # decodes into the input dtype
+    T = w.elements // w.tile
+    k = tahq.tahq_k_per_unit(cfg)
+    n_per_unit = w.seq * (w.hidden // w.tile)
+    select = 0 < k < n_per_unit
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        # the phases of tahq_encode, in order, with events between them
+        if events is not None:
+            events[0].record(stream)
+        tahq.tahq_encode_phases(cfg, d_in, codec.packed, codec.workspace, tahq.PHASE_PROLOGUE, stream)
+        if events is not None:
+            events[1].record(stream)
+        tahq.tahq_encode_phases(cfg, d_in, codec.packed, codec.workspace, tahq.PHASE_ENTROPY, stream)
+        if events is not None:
+            events[2].record(stream)
+        tahq.tahq_encode_phases(cfg, d_in, codec.packed, codec.workspace, tahq.PHASE_SELECT, stream)
+        if events is not None:
+            events[3].record(stream)
+        tahq.tahq_encode_phases(cfg, d_in, codec.packed, codec.workspace, tahq.PHASE_QUANT, stream)
+        if events is not None:
+            events[4].record(stream)
+        tahq.tahq_decode(cfg, codec.packed, codec.out, codec.out_dtype, stream)
+        if events is not None:
+            events[5].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    nbytes = w.elements * w.bytes_per_element
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+
+    names = ["prologue", "k_entropy", "select", "k_quant_pack", "k_decode"]
+    phase_ms = {nm: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs])) for i, nm in enumerate(names)}
+    gpu_ms = float(np.mean([e[0].elapsed_time(e[5]) for e in evs]))
+
+    alg = algorithmic_bytes(w, tahq.tahq_packed_size(cfg), T, select)
+    streaming = {nm: phase_ms[nm] for nm in alg if (nm != "k_entropy" or select)}
+    dominant = max(streaming, key=streaming.get)
+    achieved = alg[dominant] / (phase_ms[dominant] * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": phase_ms[dominant],
+    }
+
+    out = {
+        "metric": "encode+decode GB/s of activations on 1 MI355X; % of HBM peak",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "shape": [w.batch, w.seq, w.hidden], "storage": "bf16" if w.dtype else "f32",
+                   "tile": w.tile, "budget_bits": w.budget_bits, "out_dtype": "same as input"},
+        "pct_hbm_peak_of_activation_rate": 100.0 * value / HBM_PEAK_GBS,
+        "gpu_ms_per_step_events": gpu_ms,
+        "phase_ms": phase_ms,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

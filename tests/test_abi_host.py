@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/tahq.h declares,
+does its size arithmetic like the oracle, and rejects bad arguments before any GPU work."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import o32
+import paper_2506_01352_amd as tahq
+from paper_2506_01352_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "tahq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(tahq_[a-z0-9_]+)\s*\(", text))
+    assert {"tahq_encode", "tahq_decode", "tahq_packed_size"} <= names
+    lib = C.CDLL(tahq.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    # and the binding offers the same names
+    for n in sorted(names):
+        assert hasattr(tahq, n), n
+
+
+def test_sizes_match_the_oracle_layout_on_all_configs_and_variants():
+    cases = [(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits, 0) for w in workloads.CONFIGS]
+    cases += [(3, 7, 96, 32, 0, 3.3, 0), (3, 7, 96, 32, 0, 3.3, 1), (1, 1, 128, 128, 1, 3.5, 0), (2, 5, 640, 64, 1, 3.01, 0)]
+    for B, S, Cc, G, dt, bud, scope in cases:
+        cfg = tahq.make_config(B, S, Cc, G, dt, bud, scope=scope)
+        ocfg = o32.make_cfg(B, S, Cc, G, dt, bud, scope=scope)
+        assert tahq.tahq_packed_size(cfg) == o32.packed_size(ocfg) > 0
+        assert tahq.tahq_k_per_unit(cfg) == o32.k_per_unit(ocfg)
+        assert tahq.tahq_workspace_size(cfg) > 0
+
+
+def test_defaults_and_version():
+    cfg = tahq.tahq_config_default()
+    assert cfg.struct_size == C.sizeof(tahq.tahq_config) == 48
+    assert (cfg.tile, cfg.tau, cfg.scope) == (64, 2.0, 0)
+    assert abs(cfg.budget_bits - 3.8) < 1e-6 and abs(cfg.eps_log - 1e-8) < 1e-12
+    assert tahq.tahq_version() >> 16 == 1
+    assert tahq.tahq_status_string(0) == "ok"
+    assert "workspace" in tahq.tahq_status_string(5)
+
+
+def test_invalid_configs_are_rejected_with_size_zero():
+    bad = [
+        dict(batch=0), dict(seq=0), dict(hidden=0), dict(hidden=100), dict(tile=16), dict(tile=48),
+        dict(budget_bits=2.9), dict(budget_bits=4.1), dict(budget_bits=float("nan")), dict(dtype=2), dict(scope=2),
+    ]
+    for kw in bad:
+        args = dict(batch=2, seq=4, hidden=256, tile=64, dtype=0, budget_bits=3.5)
+        args.update(kw)
+        cfg = tahq.make_config(**args)
+        assert tahq.tahq_packed_size(cfg) == 0 and tahq.tahq_workspace_size(cfg) == 0, kw
+    cfg = tahq.make_config(2, 4, 256, 64, 0, 3.5)
+    cfg.struct_size = 44
+    assert tahq.tahq_packed_size(cfg) == 0
+
+
+def _call_encode(cfg, d_in, d_packed, cap, d_ws, wcap):
+    lib = binding._load()
+    return lib.tahq_encode(C.byref(cfg), d_in, d_packed, cap, d_ws, wcap, None)
+
+
+def _call_decode(cfg, d_packed, nbytes, d_out, out_dtype):
+    lib = binding._load()
+    return lib.tahq_decode(C.byref(cfg), d_packed, nbytes, d_out, out_dtype, None, 0, None)
+
+
+def test_argument_errors_come_back_before_anything_is_enqueued():
+    # Fake, never-dereferenced device addresses: every call below must fail in host validation.
+    cfg = tahq.make_config(2, 4, 256, 64, 0, 3.5)
+    size, ws = tahq.tahq_packed_size(cfg), tahq.tahq_workspace_size(cfg)
+    A, B_, W = 0x10000, 0x20000, 0x30000
+    assert _call_encode(cfg, None, B_, size, W, ws) == 1
+    assert _call_encode(cfg, A, None, size, W, ws) == 1
+    assert _call_encode(cfg, A, B_, size, None, ws) == 1
+    assert _call_encode(cfg, A, B_, size - 1, W, ws) == 4
+    assert _call_encode(cfg, A, B_, size, W, ws - 1) == 5
+    assert _call_encode(cfg, A + 4, B_, size, W, ws) == 6
+    assert _call_encode(cfg, A, B_ + 8, size, W, ws) == 6
+    bad = tahq.make_config(2, 4, 256, 16, 0, 3.5)
+    assert _call_encode(bad, A, B_, 1 << 20, W, 1 << 20) == 3
+    bad = tahq.make_config(2, 4, 250, 64, 0, 3.5)
+    assert _call_encode(bad, A, B_, 1 << 20, W, 1 << 20) == 2
+    assert _call_decode(cfg, None, size, B_, 0) == 1
+    assert _call_decode(cfg, A, size - 1, B_, 0) == 4
+    assert _call_decode(cfg, A, size, B_, 2) == 2
+    assert _call_decode(cfg, A, size, B_ + 2, 0) == 6
+    lib = binding._load()
+    assert lib.tahq_encode(None, A, B_, size, W, ws, None) == 1
+    assert lib.tahq_tile_entropy(C.byref(cfg), None, B_, None) == 1
+
+
+def test_parse_header_round_trips_an_oracle_stream():
+    w, x = workloads.generate(2, batch=1, seq=4)
+    ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.25, tau=3.0)
+    packed = o32.encode(ocfg, x)
+    cfg = tahq.tahq_parse_header(packed[:64].tobytes())
+    assert (cfg.batch, cfg.seq, cfg.hidden, cfg.tile, cfg.dtype, cfg.scope) == (1, 4, 2048, 64, 0, 0)
+    assert (cfg.budget_bits, cfg.tau) == (3.25, 3.0)
+    assert tahq.tahq_packed_size(cfg) == packed.size
+    broken = packed[:64].copy(); broken[0] = ord("X")
+    with pytest.raises(tahq.TahqError):
+        tahq.tahq_parse_header(broken.tobytes())

@@ -1,0 +1,265 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: bit-exact entropies (they decide the allocation), bit maps, rank tables, pivots, binary16
+metadata, payload bytes -- i.e. the whole stream -- and decoded fp32 output within 1e-6 absolute
+(in practice bit-identical), decoded bf16 output bit-identical.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import o32, o64
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module")
+def tahq():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2506_01352_amd as t
+    t.binding._load()          # fail loudly if the HIP library is missing
+    return t
+
+
+def to_device(x):
+    """Host array -> device tensor with the same bytes (bf16 bit patterns travel as int16)."""
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).cuda()
+    return torch.from_numpy(x).cuda()
+
+
+CANARY = 0xA5
+
+
+class Guarded:
+    """A device byte buffer with canary bytes on both sides."""
+
+    def __init__(self, nbytes, pad=256):
+        self.pad, self.nbytes = pad, nbytes
+        self.raw = torch.full((nbytes + 2 * pad,), CANARY, dtype=torch.uint8, device="cuda")
+        self.view = self.raw[pad:pad + nbytes]
+        assert self.view.data_ptr() % 16 == 0
+
+    def check(self):
+        r = self.raw.cpu().numpy()
+        assert (r[:self.pad] == CANARY).all() and (r[self.pad + self.nbytes:] == CANARY).all(), "out-of-bounds write"
+
+
+def run_gpu(tahq, cfg, x, out_dtype):
+    """encode + decode on the GPU with guarded buffers; returns (entropy, packed, out) on the host."""
+    d_in = to_device(x)
+    n = x.size
+    T = n // cfg.tile
+    packed = Guarded(tahq.tahq_packed_size(cfg))
+    ws = Guarded(tahq.tahq_workspace_size(cfg))
+    ent = Guarded(4 * T)
+    esz = 4 if out_dtype == tahq.F32 else 2
+    out = Guarded(esz * n)
+    tahq.tahq_tile_entropy(cfg, d_in, ent.view)
+    tahq.tahq_encode(cfg, d_in, packed.view, ws.view)
+    tahq.tahq_decode(cfg, packed.view, out.view, out_dtype)
+    torch.cuda.synchronize()
+    for g in (packed, ws, ent, out):
+        g.check()
+    H = ent.view.cpu().numpy().view(np.float32)
+    o = out.view.cpu().numpy().view(np.float32 if out_dtype == tahq.F32 else np.uint16)
+    return H, packed.view.cpu().numpy(), o
+
+
+def first_diff(a, b):
+    idx = np.nonzero(a != b)[0]
+    return None if idx.size == 0 else int(idx[0])
+
+
+def compare_streams(got, want, T, G, n_units, k):
+    """Byte-exact comparison with a section-by-section report on failure."""
+    if np.array_equal(got, want):
+        return
+    off = o64.section_offsets(T, G, n_units, k)
+    names = ["bitmap", "ranks", "pivot", "scale", "zero", "payload", "total"]
+    report = []
+    if not np.array_equal(got[:64], want[:64]):
+        report.append("header differs")
+    for a, b in zip(names[:-1], names[1:]):
+        d = first_diff(got[off[a]:off[b]], want[off[a]:off[b]])
+        if d is not None:
+            nd = int((got[off[a]:off[b]] != want[off[a]:off[b]]).sum())
+            report.append(f"{a}: {nd} bytes differ, first at +{d} (got {got[off[a] + d]:#x}, want {want[off[a] + d]:#x})")
+    raise AssertionError("stream mismatch: " + "; ".join(report))
+
+
+def check_case(tahq, x, B, S, Cc, G, dtype, budget, out_dtype=None, **kw):
+    cfg = tahq.make_config(B, S, Cc, G, dtype, budget, **kw)
+    ocfg = o32.make_cfg(B, S, Cc, G, dtype, budget, **kw)
+    out_dtype = dtype if out_dtype is None else out_dtype
+    x = np.ascontiguousarray(x).reshape(B, S, Cc)
+    H, packed, out = run_gpu(tahq, cfg, x, out_dtype)
+    T = B * S * (Cc // G)
+    wantH, _, _, _ = o32.tile_stats(ocfg, x)
+    assert np.array_equal(H.view(np.uint32), wantH.view(np.uint32)), \
+        f"entropy bits differ at tile {first_diff(H.view(np.uint32), wantH.view(np.uint32))}"
+    want = o32.encode(ocfg, x)
+    n_units = 1 if kw.get("scope", 0) else B
+    compare_streams(packed, want, T, G, n_units, o32.k_per_unit(ocfg))
+    want_out = o32.decode(ocfg, want, out_dtype)
+    if out_dtype == tahq.F32:
+        fin = np.isfinite(want_out)
+        assert np.array_equal(np.isfinite(out), fin)
+        assert np.all(np.abs(out[fin].astype(np.float64) - want_out[fin].astype(np.float64)) <= 1e-6)
+        assert np.array_equal(out.view(np.uint32)[fin], want_out.view(np.uint32)[fin])
+    else:
+        assert np.array_equal(out, want_out)
+    return packed
+
+
+# ----------------------------------------------------------------- cases
+
+SMALL = [
+    # (config index, generator shape): several tiles per block, ragged tails, n not a multiple of 64/512
+    (1, dict()),
+    (2, dict(batch=2, seq=40)),
+    (2, dict(batch=3, seq=7)),
+    (3, dict(batch=2, seq=24)),
+    (3, dict(batch=1, seq=3)),
+    (4, dict(batch=2, seq=36)),
+    (5, dict(batch=3, seq=10)),
+    (5, dict(batch=2, seq=33)),
+]
+
+
+@pytest.mark.parametrize("index,shape", SMALL)
+@pytest.mark.parametrize("budget", (None, 3.0, 3.3, 4.0))
+def test_small_workloads_bit_exact(tahq, index, shape, budget):
+    w, x = workloads.generate(index, **shape)
+    budget = w.budget_bits if budget is None else budget
+    _say(f"[case] {w.name} shape={w.batch}x{w.seq}x{w.hidden} budget={budget}")
+    check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget)
+
+
+@pytest.mark.parametrize("index,shape", [(2, dict(batch=2, seq=40)), (4, dict(batch=2, seq=36))])
+def test_output_dtype_other_than_input(tahq, index, shape):
+    w, x = workloads.generate(index, **shape)
+    other = tahq.BF16 if w.dtype == tahq.F32 else tahq.F32
+    _say(f"[case] {w.name} out_dtype={other}")
+    check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.5, out_dtype=other)
+
+
+@pytest.mark.parametrize("G", (32, 64, 128))
+@pytest.mark.parametrize("budget", (3.0, 3.5, 4.0))
+def test_edge_tiles(tahq, G, budget):
+    tiles = workloads.edge_tiles(G)
+    _say(f"[case] edge tiles G={G} budget={budget} n={len(tiles)}")
+    # as one token per tile, and as tokens of three tiles (fp32), and in bf16
+    n = len(tiles) // 3 * 3
+    check_case(tahq, tiles, 1, len(tiles), G, G, tahq.F32, budget)
+    check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, budget)
+    check_case(tahq, workloads.f32_to_bf16_bits(tiles), 1, len(tiles), G, G, tahq.BF16, budget)
+
+
+@pytest.mark.parametrize("tau", (0.0, 4.0, float("inf")))
+def test_tau_special_cases(tahq, tau):
+    w, x = workloads.generate(4, batch=1, seq=20)
+    _say(f"[case] tau={tau}")
+    check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.5, tau=tau)
+
+
+def test_whole_tensor_ranking_scope(tahq):
+    w, x = workloads.generate(2, batch=3, seq=20)
+    _say("[case] scope=1")
+    check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.4, scope=1)
+
+
+def test_massive_entropy_ties_are_broken_by_index(tahq):
+    # config-5-like tensor (20% all-zero tokens: entropy exactly 0) with a budget that puts the
+    # threshold inside the tie, plus a tensor whose tiles are all identical
+    w, x = workloads.generate(5, batch=2, seq=64)
+    _say("[case] ties at the threshold")
+    for budget in (3.1, 3.85, 3.95):
+        check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget)
+    rng = np.random.default_rng(0)
+    row = rng.standard_normal(64).astype(np.float32)
+    same = np.tile(row, (2, 50, 8))
+    check_case(tahq, same, 2, 50, 512, 64, tahq.F32, 3.37)
+
+
+def test_single_tile_and_tiny_tensors(tahq):
+    rng = np.random.default_rng(1)
+    for G in (32, 64, 128):
+        for B, S, M in ((1, 1, 1), (1, 1, 2), (2, 1, 1), (1, 5, 3)):
+            x = rng.standard_normal((B, S, M * G)).astype(np.float32)
+            x[..., 3] *= 25
+            _say(f"[case] tiny G={G} {B}x{S}x{M * G}")
+            for budget in (3.0, 3.5, 4.0):
+                check_case(tahq, x, B, S, M * G, G, tahq.F32, budget)
+
+
+def test_repeated_calls_are_deterministic_and_workspace_contents_do_not_matter(tahq):
+    w, x = workloads.generate(4, batch=2, seq=64)
+    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
+    d_in = to_device(x)
+    packed = torch.empty(tahq.tahq_packed_size(cfg), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(tahq.tahq_workspace_size(cfg), dtype=torch.uint8, device="cuda")
+    results = []
+    for fill in (0, 0xFF, 0x5A):
+        ws.fill_(fill)
+        packed.fill_(0xEE)
+        tahq.tahq_encode(cfg, d_in, packed, ws)
+        torch.cuda.synchronize()
+        results.append(packed.cpu().numpy().copy())
+    assert np.array_equal(results[0], results[1]) and np.array_equal(results[1], results[2])
+
+
+def test_side_stream(tahq):
+    w, x = workloads.generate(2, batch=1, seq=64)
+    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
+    ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
+    d_in = to_device(x)
+    codec = tahq.Codec(cfg, out_dtype=tahq.F32)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        codec.encode(d_in, stream=s)
+        codec.decode(stream=s)
+    s.synchronize()
+    want = o32.encode(ocfg, x)
+    assert np.array_equal(codec.packed.cpu().numpy(), want)
+    assert np.array_equal(codec.out.cpu().numpy(), o32.decode(ocfg, want))
+
+
+# ------------------------------------------------------- full-size configs
+
+@pytest.mark.parametrize("index", (1, 2, 3, 5, 4))
+def test_full_size_configs_bit_exact(tahq, index):
+    w, x = workloads.generate(index)
+    _say(f"[case] full size {w.name}: generated")
+    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
+    ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
+    d_in = to_device(x)
+    codec = tahq.Codec(cfg)                      # decode into the input dtype, as the benchmark does
+    T = w.elements // w.tile
+    ent = torch.empty(T, dtype=torch.float32, device="cuda")
+    tahq.tahq_tile_entropy(cfg, d_in, ent)
+    codec.encode(d_in)
+    codec.decode()
+    torch.cuda.synchronize()
+    _say("[case]   gpu done; oracle encode ...")
+    want = o32.encode(ocfg, x)
+    _say("[case]   oracle encode done")
+    compare_streams(codec.packed.cpu().numpy(), want, T, w.tile, w.batch, o32.k_per_unit(ocfg))
+    wantH, _, _, _ = o32.tile_stats(ocfg, x)
+    assert np.array_equal(ent.cpu().numpy().view(np.uint32), wantH.view(np.uint32))
+    _say("[case]   oracle decode ...")
+    want_out = o32.decode(ocfg, want, w.dtype)
+    got = codec.out.cpu()
+    got = got.numpy() if w.dtype == tahq.F32 else got.view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got.view(np.uint32 if w.dtype == tahq.F32 else np.uint16),
+                          want_out.view(np.uint32 if w.dtype == tahq.F32 else np.uint16))
