@@ -1,0 +1,314 @@
+// Top-p% tile selection (Sec. 3.2): inside every ranking unit the k tiles of highest entropy get
+// 4 bits, ties going to the lower tile index.  Exact, deterministic, no sort:
+//
+//   * entropies map to order-preserving 32-bit keys;
+//   * three histogram passes (11 + 11 + 10 bits, from the top) find the k-th largest key K*
+//     and how many tiles equal to K* are still wanted (`take`);
+//   * per segment of tiles, counts of keys == K* and > K* ; their prefix sums give every tile
+//     its place among the equal keys (index order) and every 64-tile group its rank-table entry.
+//
+// Kernels never wait on each other inside a launch: every dependency is a launch boundary, and the
+// small reductions a later kernel needs (which bin holds the k-th key, prefix over segments) are
+// recomputed by every block from a few KB of global data.
+#pragma once
+#include "tahq_common.hpp"
+
+namespace tahq {
+
+__device__ __forceinline__ uint32_t order_key(float h)
+{
+    const uint32_t u = __float_as_uint(h);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Inclusive scan over the 64 lanes of a wavefront.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)v, off, 64);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// selection state of one ranking unit (uint32[8] in the workspace)
+enum { ST_BIN0 = 0, ST_BIN1 = 1, ST_BIN2 = 2, ST_KREM0 = 3, ST_KREM1 = 4, ST_KEY = 5, ST_TAKE = 6 };
+
+// Which bin of a 2048-bin histogram holds the `want`-th largest key (bins counted from the top),
+// and how many keys are still wanted inside that bin.  Run by one full wavefront; lane l owns the
+// 32 bins 2047-32l .. 2016-32l.  Result is returned in every lane.
+__device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint32_t want, uint32_t *bin,
+                                         uint32_t *rem)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t c[32], mine = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) { c[i] = hist[kHistBins - 1 - (lane * 32 + i)]; mine += c[i]; }
+    uint32_t above = wave_incl_scan(mine) - mine;      // keys in bins above my 32
+    uint32_t found_bin = 0, found_rem = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        if (!found && above < want && want <= above + c[i]) {
+            found = true;
+            found_bin = kHistBins - 1 - (lane * 32 + i);
+            found_rem = want - above;
+        }
+        above += c[i];
+    }
+    // exactly one lane finds it when 1 <= want <= total; otherwise fall back to bin 0 / 0 wanted
+    const uint64_t who = __ballot(found);
+    const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
+    *bin = (uint32_t)__shfl((int)found_bin, src, 64);
+    *rem = (uint32_t)__shfl((int)found_rem, src, 64);
+}
+
+// One radix pass.  Digits: pass 0 = key bits 31..21, pass 1 = bits 20..10, pass 2 = bits 9..0.
+// Pass p > 0 first derives, from the histogram of pass p-1, the bin chosen there (every block does
+// this; block 0 of the unit also records it in `state`), then histograms digit p of the keys whose
+// higher digits match.  PEEL > 0 aggregates equal digits inside a wavefront before touching LDS
+// (pass 0 sees only a handful of distinct digits, which would serialize the LDS atomics).
+template <int PASS, int PEEL>
+__global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H, uint32_t n, uint32_t k,
+                                                    uint32_t *__restrict__ hist, uint32_t *__restrict__ state)
+{
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ uint32_t chosen[2];
+    const uint32_t u = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint32_t *uh = hist + ((uint64_t)u * 3 + PASS) * kHistBins;
+    uint32_t *ust = state + (uint64_t)u * 8;
+    const float *uH = H + (uint64_t)u * n;
+
+    for (int i = tid; i < (int)kHistBins; i += 256) lh[i] = 0;
+
+    uint32_t want_hi = 0;
+    if (PASS > 0) {
+        if (tid < 64) {
+            const uint32_t want = PASS == 1 ? k : ust[ST_KREM0];
+            uint32_t bin, rem;
+            pick_bin(uh - kHistBins, want, &bin, &rem);
+            if (lane == 0) {
+                chosen[0] = bin;
+                chosen[1] = rem;
+                if (blockIdx.x == 0) { ust[ST_BIN0 + PASS - 1] = bin; ust[ST_KREM0 + PASS - 1] = rem; }
+            }
+        }
+        __syncthreads();
+        want_hi = PASS == 1 ? chosen[0] : ((ust[ST_BIN0] << 11) | chosen[0]);
+    } else {
+        __syncthreads();
+    }
+
+    constexpr int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
+    constexpr uint32_t mask = PASS == 2 ? 1023u : 2047u;
+    constexpr int hi_shift = PASS == 1 ? 21 : 10;
+
+    // every thread walks the unit's keys in steps of the grid; four loads are in flight at a time
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (uint64_t base = (uint64_t)blockIdx.x * 256 + tid; base < n; base += 4 * stride) {
+        uint32_t key[4];
+        bool ok[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint64_t i = base + r * stride;
+            ok[r] = i < n;
+            key[r] = ok[r] ? order_key(uH[i]) : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            bool active = ok[r] && (PASS == 0 || (key[r] >> hi_shift) == want_hi);
+            const uint32_t bin = (key[r] >> shift) & mask;
+#pragma unroll 1
+            for (int it = 0; it < PEEL; ++it) {
+                const uint64_t am = __ballot(active);
+                if (am == 0) break;
+                const int leader = (int)__ffsll((unsigned long long)am) - 1;
+                const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+                const bool same = active && bin == lb;
+                const uint64_t sm = __ballot(same);
+                if (lane == leader) atomicAdd(&lh[lb], (uint32_t)__popcll(sm));
+                active = active && !same;
+            }
+            if (active) atomicAdd(&lh[bin], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < (int)kHistBins; i += 256)
+        if (lh[i]) atomicAdd(&uh[i], lh[i]);
+}
+
+// Per segment of kSegTiles tiles (one wavefront each): how many keys equal K* and how many exceed it.
+// K* and `take` come from the pass-2 histogram; every block derives them, block 0 records them.
+__global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, uint32_t n, uint32_t nseg,
+                                                   const uint32_t *__restrict__ hist, uint32_t *__restrict__ state,
+                                                   uint32_t *__restrict__ seg)
+{
+    __shared__ uint32_t chosen[2];
+    const uint32_t u = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t *ust = state + (uint64_t)u * 8;
+    if (tid < 64) {
+        uint32_t bin, rem;
+        pick_bin(hist + ((uint64_t)u * 3 + 2) * kHistBins, ust[ST_KREM1], &bin, &rem);
+        const uint32_t key = (ust[ST_BIN0] << 21) | (ust[ST_BIN1] << 10) | bin;
+        if (lane == 0) {
+            chosen[0] = key;
+            chosen[1] = rem;
+            if (blockIdx.x == 0) { ust[ST_BIN2] = bin; ust[ST_KEY] = key; ust[ST_TAKE] = rem; }
+        }
+    }
+    __syncthreads();
+    const uint32_t thr = chosen[0];
+    const uint32_t s = blockIdx.x * 4 + wave;
+    if (s >= nseg) return;
+    const float *uH = H + (uint64_t)u * n;
+    uint32_t eq = 0, gt = 0;
+    for (int r0 = 0; r0 < (int)(kSegTiles / 64); r0 += 8) {
+        uint32_t key[8];
+        bool ok[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint64_t j = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
+            ok[r] = j < n;
+            key[r] = ok[r] ? order_key(uH[j]) : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            eq += (uint32_t)__popcll(__ballot(ok[r] && key[r] == thr));
+            gt += (uint32_t)__popcll(__ballot(ok[r] && key[r] > thr));
+        }
+    }
+    if (lane == 0) {
+        seg[((uint64_t)u * nseg + s) * 2 + 0] = eq;
+        seg[((uint64_t)u * nseg + s) * 2 + 1] = gt;
+    }
+}
+
+// Width bit of every tile, rank-table entries, and the bit map itself when units start on 64-tile
+// boundaries (otherwise one byte per tile goes to `sel_bytes` and k_bitmap_pack follows).
+// A block owns 4 consecutive segments.  Its first wavefront sums the segment counts that precede
+// the block: equal keys before it (they are taken in index order until `take` are used up) and
+// 4-bit tiles before it (every earlier ranking unit contributes exactly k).
+__global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uint32_t n, uint32_t k, uint32_t nseg,
+                                                const uint32_t *__restrict__ state,
+                                                const uint32_t *__restrict__ seg,
+                                                uint64_t *__restrict__ bitmap, uint32_t *__restrict__ ranks,
+                                                uint8_t *__restrict__ sel_bytes, int aligned)
+{
+    __shared__ uint32_t base_eq[4], base_rank[4];
+    const uint32_t u = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t *ust = state + (uint64_t)u * 8;
+    const uint32_t thr = ust[ST_KEY], take = ust[ST_TAKE];
+    const uint32_t *useg = seg + (uint64_t)u * nseg * 2;
+    const uint32_t s0 = blockIdx.x * 4;
+
+    if (tid < 64) {
+        // lane l owns the run of segments [l*run, (l+1)*run) of the s0 segments before this block
+        const uint32_t run = (s0 + 63) / 64;
+        const uint32_t lo = (uint32_t)lane * run;
+        const uint32_t hi = lo + run < s0 ? lo + run : s0;
+        uint32_t eq_sum = 0;
+        for (uint32_t i = lo; i < hi; ++i) eq_sum += useg[2 * i];
+        uint32_t eq_before = wave_incl_scan(eq_sum) - eq_sum;
+        uint32_t sel_sum = 0;
+        for (uint32_t i = lo; i < hi; ++i) {
+            const uint32_t eq = useg[2 * i], gt = useg[2 * i + 1];
+            const uint32_t left = eq_before < take ? take - eq_before : 0u;
+            sel_sum += gt + (eq < left ? eq : left);
+            eq_before += eq;
+        }
+        const uint32_t sel_incl = wave_incl_scan(sel_sum);
+        // totals over all preceding segments sit in lane 63
+        uint32_t eq_run = (uint32_t)__shfl((int)eq_before, 63, 64);
+        uint32_t rank_run = u * k + (uint32_t)__shfl((int)sel_incl, 63, 64);
+        // the block's own four segments, in order
+        for (int w = 0; w < 4; ++w) {
+            if (lane == 0) { base_eq[w] = eq_run; base_rank[w] = rank_run; }
+            if (s0 + w < nseg) {
+                const uint32_t eq = useg[2 * (s0 + w)], gt = useg[2 * (s0 + w) + 1];
+                const uint32_t left = eq_run < take ? take - eq_run : 0u;
+                rank_run += gt + (eq < left ? eq : left);
+                eq_run += eq;
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t s = s0 + wave;
+    if (s >= nseg) return;
+    const float *uH = H + (uint64_t)u * n;
+    uint32_t eq_run = base_eq[wave], rank_run = base_rank[wave];
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (int r0 = 0; r0 < (int)(kSegTiles / 64); r0 += 8) {
+        uint32_t key[8];
+        bool ok[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
+            ok[r] = jl < n;
+            key[r] = ok[r] ? order_key(uH[jl]) : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
+            const bool eq = ok[r] && key[r] == thr;
+            const uint64_t eq_mask = __ballot(eq);
+            const bool sel = ok[r] && (key[r] > thr || (eq && eq_run + (uint32_t)__popcll(eq_mask & below) < take));
+            const uint64_t sel_mask = __ballot(sel);
+            const uint64_t jg = (uint64_t)u * n + jl;     // tile index in the tensor
+            if (aligned) {
+                if (lane == 0 && ok[r]) { bitmap[jg >> 6] = sel_mask; ranks[jg >> 6] = rank_run; }
+            } else if (ok[r]) {
+                sel_bytes[jg] = sel ? 1 : 0;
+                if ((jg & 63u) == 0) ranks[jg >> 6] = rank_run + (uint32_t)__popcll(sel_mask & below);
+            }
+            eq_run += (uint32_t)__popcll(eq_mask);
+            rank_run += (uint32_t)__popcll(sel_mask);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_bitmap_pack(const uint8_t *__restrict__ sel_bytes, uint32_t T,
+                                                     uint64_t *__restrict__ bitmap)
+{
+    const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint64_t word = __ballot(j < T && sel_bytes[j < T ? j : 0] != 0);
+    if ((threadIdx.x & 63) == 0 && (j >> 6) < ((uint64_t)T + 63) / 64) bitmap[j >> 6] = word;
+}
+
+// Budget 3.0 or 4.0: every tile has the same width.
+__global__ __launch_bounds__(256) void k_bitmap_const(uint32_t T, int all4, uint64_t *__restrict__ bitmap,
+                                                      uint32_t *__restrict__ ranks)
+{
+    const uint64_t w = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint64_t words = ((uint64_t)T + 63) / 64;
+    if (w >= words) return;
+    uint64_t bits = 0;
+    if (all4) {
+        const uint64_t left = (uint64_t)T - w * 64;
+        bits = left >= 64 ? ~0ull : ((1ull << left) - 1ull);
+    }
+    bitmap[w] = bits;
+    ranks[w] = all4 ? (uint32_t)(w * 64) : 0u;
+}
+
+// Header, zeroed section padding, zeroed histograms.
+struct HeaderWords { uint32_t w[16]; };
+struct PadList { uint64_t begin[5]; uint32_t len[5]; };
+
+__global__ __launch_bounds__(256) void k_prologue(uint8_t *__restrict__ packed, HeaderWords hdr, PadList pads,
+                                                  uint32_t *__restrict__ zero_base, uint32_t zero_words)
+{
+    const uint32_t gid = blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < 16) reinterpret_cast<uint32_t *>(packed)[threadIdx.x] = hdr.w[threadIdx.x];
+        for (int s = 0; s < 5; ++s)
+            if (threadIdx.x < pads.len[s]) packed[pads.begin[s] + threadIdx.x] = 0;
+    }
+    for (uint32_t i = gid; i < zero_words; i += gridDim.x * 256) zero_base[i] = 0u;
+}
+
+}  // namespace tahq
