@@ -25,28 +25,48 @@ inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 
 inline uint32_t blocks_for(uint64_t threads) { return (uint32_t)((threads + 255) / 256); }
 
-template <typename F32K, typename BF16K>
-inline void pick(uint32_t dtype, F32K f, BF16K g) { if (dtype == TAHQ_BF16) g(); else f(); }
+// Dispatch on the tile width G and on a dtype flag (bf16 or not) to a functor template.
+template <template <int, bool> class F, typename... Args>
+inline void dispatch(uint32_t G, bool bf16, Args... args)
+{
+    if (G == 32) { if (bf16) F<32, true>::run(args...); else F<32, false>::run(args...); }
+    else if (G == 64) { if (bf16) F<64, true>::run(args...); else F<64, false>::run(args...); }
+    else { if (bf16) F<128, true>::run(args...); else F<128, false>::run(args...); }
+}
 
-#define TAHQ_LAUNCH_G(KERNEL, G_, FLAG, grid, stream, ...)                                           \
-    do {                                                                                             \
-        if ((G_) == 32) {                                                                            \
-            if (FLAG) hipLaunchKernelGGL((KERNEL<32, true>), grid, dim3(256), 0, stream, __VA_ARGS__);  \
-            else hipLaunchKernelGGL((KERNEL<32, false>), grid, dim3(256), 0, stream, __VA_ARGS__);      \
-        } else if ((G_) == 64) {                                                                     \
-            if (FLAG) hipLaunchKernelGGL((KERNEL<64, true>), grid, dim3(256), 0, stream, __VA_ARGS__);  \
-            else hipLaunchKernelGGL((KERNEL<64, false>), grid, dim3(256), 0, stream, __VA_ARGS__);      \
-        } else {                                                                                     \
-            if (FLAG) hipLaunchKernelGGL((KERNEL<128, true>), grid, dim3(256), 0, stream, __VA_ARGS__); \
-            else hipLaunchKernelGGL((KERNEL<128, false>), grid, dim3(256), 0, stream, __VA_ARGS__);     \
-        }                                                                                            \
-    } while (0)
+template <int G, bool BF16>
+struct LaunchEntropy {
+    static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, hipStream_t st)
+    {
+        using B = Batch<G, BF16 ? 2 : 4>;
+        hipLaunchKernelGGL((k_entropy<G, BF16>), dim3((T + B::TILES - 1) / B::TILES), dim3(B::TILES), 0, st, d_in, d_H,
+                           T, eps_l1, eps_log);
+    }
+};
+
+template <int G, bool BF16>
+struct LaunchQuantPack {
+    static void run(const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio, hipStream_t st)
+    {
+        using B = Batch<G, BF16 ? 2 : 4>;
+        hipLaunchKernelGGL((k_quant_pack<G, BF16>), dim3((T + B::TILES - 1) / B::TILES), dim3(B::TILES), 0, st, d_in,
+                           packed, lay, T, tau, eps_ratio);
+    }
+};
+
+template <int G, bool BF16>
+struct LaunchDecode {
+    static void run(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, hipStream_t st)
+    {
+        using B = Batch<G, BF16 ? 2 : 4>;
+        hipLaunchKernelGGL((k_decode<G, BF16>), dim3((T + B::TILES - 1) / B::TILES), dim3(B::TILES), 0, st, packed,
+                           d_out, lay, T);
+    }
+};
 
 void launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, hipStream_t st)
 {
-    const uint32_t grid = blocks_for(s.T * (s.G / 8));
-    TAHQ_LAUNCH_G(k_entropy, s.G, s.dtype == TAHQ_BF16, dim3(grid), st, d_in, d_H, (uint32_t)s.T,
-                  cfg->eps_l1, cfg->eps_log);
+    dispatch<LaunchEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_H, (uint32_t)s.T, cfg->eps_l1, cfg->eps_log, st);
 }
 
 }  // namespace
@@ -183,9 +203,8 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     }
 
     if (phases & TAHQ_PHASE_QUANT) {
-        const uint32_t grid = blocks_for(s.T * (s.G / 8));
-        TAHQ_LAUNCH_G(k_quant_pack, s.G, s.dtype == TAHQ_BF16, dim3(grid), st, d_in, packed, lay, (uint32_t)s.T,
-                      cfg->tau, cfg->eps_ratio);
+        dispatch<LaunchQuantPack>(s.G, s.dtype == TAHQ_BF16, d_in, packed, lay, (uint32_t)s.T, cfg->tau,
+                                  cfg->eps_ratio, st);
     }
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
@@ -211,10 +230,8 @@ tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t pac
     make_layout(s, &lay);
     if (packed_bytes < lay.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
     if (misaligned(d_packed) || misaligned(d_out)) return TAHQ_ERR_MISALIGNED;
-    const uint32_t grid = blocks_for(s.T * (s.G / 8));
-    hipStream_t st = (hipStream_t)stream;
-    TAHQ_LAUNCH_G(k_decode, s.G, out_dtype == TAHQ_BF16, dim3(grid), st, static_cast<const uint8_t *>(d_packed),
-                  d_out, lay, (uint32_t)s.T);
+    dispatch<LaunchDecode>(s.G, out_dtype == TAHQ_BF16, static_cast<const uint8_t *>(d_packed), d_out, lay,
+                           (uint32_t)s.T, (hipStream_t)stream);
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
 
