@@ -34,13 +34,25 @@ inline void dispatch(uint32_t G, bool bf16, Args... args)
     else { if (bf16) F<128, true>::run(args...); else F<128, false>::run(args...); }
 }
 
+// Persistent launch: as many workgroups as fit on the device at once (or fewer, if there are fewer batches).
+inline uint32_t resident_blocks(const void *kernel, int threads)
+{
+    int dev = 0, cus = 256, per_cu = 1;
+    if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu <= 0) per_cu = 1;
+    return (uint32_t)cus * (uint32_t)per_cu;
+}
+
 template <int G, bool BF16>
 struct LaunchEntropy {
     static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
-        hipLaunchKernelGGL((k_entropy<G, BF16>), dim3((T + B::TILES - 1) / B::TILES), dim3(B::TILES), 0, st, d_in, d_H,
-                           T, eps_l1, eps_log);
+        const uint32_t nb = (T + B::TILES - 1) / B::TILES;
+        static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_entropy<G, BF16>), B::TILES);
+        hipLaunchKernelGGL((k_entropy<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, d_in, d_H, T,
+                           eps_l1, eps_log);
     }
 };
 
@@ -49,8 +61,9 @@ struct LaunchQuantPack {
     static void run(const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
-        hipLaunchKernelGGL((k_quant_pack<G, BF16>), dim3((T + B::TILES - 1) / B::TILES), dim3(B::TILES), 0, st, d_in,
-                           packed, lay, T, tau, eps_ratio);
+        const uint32_t nb = (T + B::TILES - 1) / B::TILES;
+        hipLaunchKernelGGL((k_quant_pack<G, BF16>), dim3(nb), dim3(B::TILES), 0, st, d_in, packed, lay, T, tau,
+                           eps_ratio);
     }
 };
 
@@ -59,8 +72,9 @@ struct LaunchDecode {
     static void run(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
-        hipLaunchKernelGGL((k_decode<G, BF16>), dim3((T + B::TILES - 1) / B::TILES), dim3(B::TILES), 0, st, packed,
-                           d_out, lay, T);
+        const uint32_t nb = (T + B::TILES - 1) / B::TILES;
+        static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_decode<G, BF16>), B::TILES);
+        hipLaunchKernelGGL((k_decode<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, packed, d_out, lay, T);
     }
 };
 

@@ -21,34 +21,44 @@ struct Batch {
     static constexpr int LDS_BYTES = TILES * STRIDE;
 };
 
-// Coalesced copy of `nvalid` tiles from global memory into padded LDS rows.
-template <int G, int ESIZE>
-__device__ __forceinline__ void stage_in(const void *__restrict__ in, uint64_t j0, uint32_t nvalid, uint8_t *lds)
+// A batch's tiles travel global -> registers -> padded LDS rows, in two steps, so that the loads of the
+// next batch can be in flight while the current one is being processed.  Thread t moves the 16-byte
+// chunks t, t + TILES, t + 2 TILES, ... of the batch (coalesced).  FULL: all TILES tiles exist, no
+// per-thread conditions (so that the compiler can count outstanding memory operations exactly).
+template <int G, int ESIZE, bool FULL>
+__device__ __forceinline__ void load_batch(const void *__restrict__ in, uint64_t j0, uint32_t nvalid,
+                                           uint4 (&v)[Batch<G, ESIZE>::CHUNKS])
 {
     using B = Batch<G, ESIZE>;
-    constexpr int UNR = B::CHUNKS < 8 ? B::CHUNKS : 8;
     const uint8_t *src = static_cast<const uint8_t *>(in) + j0 * B::BYTES;
     const int tid = threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < B::CHUNKS; i += UNR) {
-        uint4 v[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const uint32_t q = (uint32_t)(i + u) * B::TILES + tid;
-            v[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (q / B::CHUNKS < nvalid) v[u] = *reinterpret_cast<const uint4 *>(src + (uint64_t)q * 16);
-        }
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const uint32_t q = (uint32_t)(i + u) * B::TILES + tid;
-            const uint32_t tile = q / B::CHUNKS, sub = q % B::CHUNKS;
-            if (tile < nvalid) *reinterpret_cast<uint4 *>(lds + tile * B::STRIDE + sub * 16) = v[u];
+    for (int i = 0; i < B::CHUNKS; ++i) {
+        const uint32_t q = (uint32_t)i * B::TILES + tid;
+        if constexpr (FULL) {
+            v[i] = *reinterpret_cast<const uint4 *>(src + (uint64_t)q * 16);
+        } else {
+            v[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (q / B::CHUNKS < nvalid) v[i] = *reinterpret_cast<const uint4 *>(src + (uint64_t)q * 16);
         }
     }
 }
 
+template <int G, int ESIZE, bool FULL>
+__device__ __forceinline__ void store_batch(const uint4 (&v)[Batch<G, ESIZE>::CHUNKS], uint32_t nvalid, uint8_t *lds)
+{
+    using B = Batch<G, ESIZE>;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < B::CHUNKS; ++i) {
+        const uint32_t q = (uint32_t)i * B::TILES + tid;
+        const uint32_t tile = q / B::CHUNKS, sub = q % B::CHUNKS;
+        if (FULL || tile < nvalid) *reinterpret_cast<uint4 *>(lds + tile * B::STRIDE + sub * 16) = v[i];
+    }
+}
+
 // Coalesced copy of `nvalid` tiles from padded LDS rows to global memory.
-template <int G, int ESIZE>
+template <int G, int ESIZE, bool FULL>
 __device__ __forceinline__ void stage_out(void *__restrict__ out, uint64_t j0, uint32_t nvalid, const uint8_t *lds)
 {
     using B = Batch<G, ESIZE>;
@@ -58,7 +68,7 @@ __device__ __forceinline__ void stage_out(void *__restrict__ out, uint64_t j0, u
     for (int i = 0; i < B::CHUNKS; ++i) {
         const uint32_t q = (uint32_t)i * B::TILES + tid;
         const uint32_t tile = q / B::CHUNKS, sub = q % B::CHUNKS;
-        if (tile < nvalid)
+        if (FULL || tile < nvalid)
             *reinterpret_cast<uint4 *>(dst + (uint64_t)q * 16) = *reinterpret_cast<const uint4 *>(lds + tile * B::STRIDE + sub * 16);
     }
 }
@@ -115,21 +125,12 @@ __device__ __forceinline__ void butterfly(float *x)
 
 // -------------------------------------------------------------- K0: entropy
 
+// Eq. 1-2 for my tile, read from its LDS row.
 template <int G, bool BF16>
-__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
-void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, float eps_l1, float eps_log)
+__device__ __forceinline__ float entropy_of_row(const uint8_t *row, float eps_l1, float eps_log)
 {
-    using B = Batch<G, BF16 ? 2 : 4>;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
-    const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
-    const uint32_t left = (uint32_t)(T - j0);
-    const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
-    stage_in<G, BF16 ? 2 : 4>(in, j0, nvalid, lds);
-    __syncthreads();
-    if (threadIdx.x >= nvalid) return;
-
     float a[G];
-    read_tile<G, BF16>(lds + threadIdx.x * B::STRIDE, a);
+    read_tile<G, BF16>(row, a);
 #pragma unroll
     for (int k = 0; k < G; ++k) a[k] = __builtin_fabsf(a[k]);
     const float L1 = tree_sum<G>(a);
@@ -140,7 +141,50 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
         const float u = p + eps_log;
         a[k] = p * log_contract(u);
     }
-    H[j0 + threadIdx.x] = 0.0f - tree_sum<G>(a);
+    return 0.0f - tree_sum<G>(a);
+}
+
+// Persistent workgroups: workgroup w handles the full batches w, w + gridDim.x, ...  The next batch's
+// loads are issued before the current batch is processed, and a batch's result is stored one iteration
+// later, just before those loads, so that no wait for loads ever has a younger store in front of it.
+// The ragged last batch (T not a multiple of TILES) is handled after the loop by one workgroup.
+template <int G, bool BF16>
+__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
+void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, float eps_l1, float eps_log)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    using B = Batch<G, ES>;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
+    const int tid = threadIdx.x;
+    const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
+    const uint8_t *row = lds + tid * B::STRIDE;
+
+    uint4 v[B::CHUNKS];
+    uint32_t batch = blockIdx.x;
+    if (batch < nfull) load_batch<G, ES, true>(in, (uint64_t)batch * B::TILES, B::TILES, v);
+    float h_prev = 0.0f;
+    uint64_t j_prev = 0;
+    bool have_prev = false;
+    for (; batch < nfull; batch += gridDim.x) {
+        store_batch<G, ES, true>(v, B::TILES, lds);
+        __syncthreads();
+        if (have_prev) H[j_prev] = h_prev;
+        const uint32_t next = batch + gridDim.x;
+        if (next < nfull) load_batch<G, ES, true>(in, (uint64_t)next * B::TILES, B::TILES, v);
+        h_prev = entropy_of_row<G, BF16>(row, eps_l1, eps_log);
+        j_prev = (uint64_t)batch * B::TILES + tid;
+        have_prev = true;
+        __syncthreads();
+    }
+    if (have_prev) H[j_prev] = h_prev;
+
+    if (tail != 0 && blockIdx.x == nfull % gridDim.x) {
+        const uint64_t j0 = (uint64_t)nfull * B::TILES;
+        load_batch<G, ES, false>(in, j0, tail, v);
+        store_batch<G, ES, false>(v, tail, lds);
+        __syncthreads();
+        if ((uint32_t)tid < tail) H[j0 + tid] = entropy_of_row<G, BF16>(row, eps_l1, eps_log);
+    }
 }
 
 // ------------------------------------ K3: transform + quantize + pack
@@ -214,6 +258,143 @@ __device__ __forceinline__ void top2(const uint8_t *row, float *a1_out, float *a
     }
 }
 
+// What a workgroup must know about a batch before it can place payload: the bit map words of the
+// batch's 64-tile groups and the rank-table entry of the first one.
+template <int TILES>
+struct BatchMeta {
+    static constexpr int WORDS = (TILES + 63) / 64;
+    uint64_t word[WORDS];
+    uint32_t rank0;
+};
+
+// `lane_zero` is a per-lane zero the compiler cannot see through: it turns these uniform loads into
+// vector loads, which are counted in order with the other global loads (scalar loads are not, and a
+// wait for LDS data would also wait for them).
+template <int TILES>
+__device__ __forceinline__ void load_meta(const uint8_t *__restrict__ packed, const Layout &lay, uint64_t j0, uint32_t T,
+                                          uint32_t lane_zero, BatchMeta<TILES> &m)
+{
+    const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap) + lane_zero;
+    const uint32_t *ranks = reinterpret_cast<const uint32_t *>(packed + lay.ranks) + lane_zero;
+#pragma unroll
+    for (int w = 0; w < BatchMeta<TILES>::WORDS; ++w) {
+        const uint64_t jw = (j0 >> 6) + w;
+        m.word[w] = jw * 64 < T ? bitmap[jw] : 0ull;
+    }
+    m.rank0 = ranks[j0 >> 6];
+}
+
+// Width of my tile, its payload position inside the batch (in units of G/8 bytes), and the number of
+// 4-bit tiles in the batch.
+template <int TILES>
+__device__ __forceinline__ void tile_pos(const BatchMeta<TILES> &m, int tid, uint32_t *b, uint32_t *rel, uint32_t *total4)
+{
+    uint32_t bb = 3, rr = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < BatchMeta<TILES>::WORDS; ++w) {
+        if (w == (tid >> 6)) {
+            const uint32_t bit = (uint32_t)tid & 63u;
+            bb = 3u + (uint32_t)((m.word[w] >> bit) & 1ull);
+            rr = 3u * (uint32_t)tid + tot + (uint32_t)__popcll(m.word[w] & ((1ull << bit) - 1ull));
+        }
+        tot += (uint32_t)__popcll(m.word[w]);
+    }
+    *b = bb; *rel = rr; *total4 = tot;
+}
+
+// Everything the encoder does to my tile once its width b is known: Eq. 3 (outlier test), P_d and
+// Eq. 4 on outlier tiles, range, quantizer parameters, codes, and the tile's LSB-first bit string
+// written as b units at `dst` (LDS).  Returns scale | zero << 16 and the pivot byte.
+template <int G, bool BF16>
+__device__ __forceinline__ void quantize_row(uint8_t *row, uint32_t b, typename Unit<G>::type *dst, float tau,
+                                             float eps_ratio, uint32_t *meta16, uint32_t *pivot)
+{
+    using U = typename Unit<G>::type;
+    float a1, a2;
+    uint32_t d;
+    top2<G, BF16>(row, &a1, &a2, &d);
+    const bool flag = a1 > tau * (a2 + eps_ratio);
+    if (flag && d != 0) {
+        // P_d: swap elements 0 and d inside my LDS row
+        if constexpr (BF16) {
+            uint16_t *r16 = reinterpret_cast<uint16_t *>(row);
+            const uint16_t v0 = r16[0], vd = r16[d];
+            r16[0] = vd; r16[d] = v0;
+        } else {
+            float *r32 = reinterpret_cast<float *>(row);
+            const float v0 = r32[0], vd = r32[d];
+            r32[0] = vd; r32[d] = v0;
+        }
+    }
+    float x[G];
+    read_tile<G, BF16>(row, x);
+    if (flag) {
+        butterfly<G>(x);
+#pragma unroll
+        for (int k = 0; k < G; ++k) x[k] = x[k] * TileConst<G>::c;
+    }
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int k = 1; k < G; ++k) { mn = __builtin_fminf(mn, x[k]); mx = __builtin_fmaxf(mx, x[k]); }
+    mn = mn + 0.0f;
+    mx = mx + 0.0f;
+
+    // asymmetric quantizer, binary16 metadata rounded outwards
+    const float Lv = (b == 4u) ? 15.0f : 7.0f;
+    const uint32_t z16 = f16_down(mn);
+    const float mnf = f16_widen(z16);
+    const float s = (mx - mnf) / Lv;
+    uint32_t s16 = f16_up(s);
+    if ((s16 & 0x7fffu) == 0) s16 = 0x3c00u;
+    const float sf = f16_widen(s16);
+    const float rcp = 1.0f / sf;
+
+    // codes, four at a time: q0 + m q1 + m^2 q2 + m^3 q3 is an exact integer below 2^16 in fp32
+    const float m1 = (b == 4u) ? 16.0f : 8.0f;
+    const float m2 = m1 * m1, m3 = m2 * m1;
+    uint32_t g4[G / 4];
+#pragma unroll
+    for (int g = 0; g < G / 4; ++g) {
+        float q[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            q[i] = __builtin_fminf(__builtin_fmaxf(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f), Lv);
+        const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
+        g4[g] = (uint32_t)acc;
+    }
+    // LSB-first bit string of the tile as dwords
+    uint32_t dw[G / 8];
+    if (b == 4u) {
+#pragma unroll
+        for (int i = 0; i < G / 8; ++i) dw[i] = g4[2 * i] | (g4[2 * i + 1] << 16);
+    } else {
+        // 12-bit groups: eight of them fill three dwords
+#pragma unroll
+        for (int i = 0; i < G / 32; ++i) {
+            const uint32_t *p = g4 + 8 * i;
+            dw[3 * i + 0] = p[0] | (p[1] << 12) | (p[2] << 24);
+            dw[3 * i + 1] = (p[2] >> 8) | (p[3] << 4) | (p[4] << 16) | (p[5] << 28);
+            dw[3 * i + 2] = (p[5] >> 4) | (p[6] << 8) | (p[7] << 20);
+        }
+#pragma unroll
+        for (int i = 3 * (G / 32); i < G / 8; ++i) dw[i] = 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (u < 3 || b == 4u) {
+            if constexpr (G == 32) dst[u] = dw[u];
+            else if constexpr (G == 64) dst[u] = make_uint2(dw[2 * u], dw[2 * u + 1]);
+            else dst[u] = make_uint4(dw[4 * u], dw[4 * u + 1], dw[4 * u + 2], dw[4 * u + 3]);
+        }
+    }
+    (void)sizeof(U);
+    *meta16 = s16 | (z16 << 16);
+    *pivot = flag ? (0x80u | d) : 0u;
+}
+
+// One workgroup per batch of TILES tiles.  (This kernel is bound by vector-ALU issue; keeping it
+// non-persistent keeps its register count down, and its loads are covered by the other resident
+// workgroups.)
 template <int G, bool BF16>
 __global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
 void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Layout lay, uint32_t T, float tau,
@@ -228,126 +409,136 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
     const uint32_t left = (uint32_t)(T - j0);
     const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
-    stage_in<G, ES>(in, j0, nvalid, lds);
+    const bool full = nvalid == (uint32_t)B::TILES;
 
-    // width and payload position of my tile: bit map word and rank-table entry of my 64-tile group
-    const uint64_t j = j0 + tid;
-    const bool valid = (uint32_t)tid < nvalid;
-    const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap);
-    const uint32_t *ranks = reinterpret_cast<const uint32_t *>(packed + lay.ranks);
-    const uint32_t rank0 = ranks[j0 >> 6];
-    uint32_t b = 3, rel = 0;          // rel: my payload position inside the batch, in units
-    uint32_t total4 = 0;              // 4-bit tiles in the batch
-#pragma unroll
-    for (int w = 0; w < (B::TILES + 63) / 64; ++w) {
-        const uint64_t jw = (j0 >> 6) + w;
-        const uint64_t word = jw * 64 < T ? bitmap[jw] : 0ull;
-        if (w == (tid >> 6)) {
-            const uint32_t bit = (uint32_t)tid & 63u;
-            b = 3u + (uint32_t)((word >> bit) & 1ull);
-            rel = 3u * (uint32_t)tid + total4 + (uint32_t)__popcll(word & ((1ull << bit) - 1ull));
-        }
-        total4 += (uint32_t)__popcll(word);
+    uint4 v[B::CHUNKS];
+    if (full) load_batch<G, ES, true>(in, j0, nvalid, v);
+    else load_batch<G, ES, false>(in, j0, nvalid, v);
+    BatchMeta<B::TILES> meta;
+    load_meta<B::TILES>(packed, lay, j0, T, 0u, meta);
+    if (full) store_batch<G, ES, true>(v, nvalid, lds);
+    else store_batch<G, ES, false>(v, nvalid, lds);
+    uint32_t b, rel, total4;
+    tile_pos<B::TILES>(meta, tid, &b, &rel, &total4);
+    __syncthreads();
+
+    if ((uint32_t)tid < nvalid) {
+        uint32_t meta16, pivot;
+        quantize_row<G, BF16>(lds + tid * B::STRIDE, b, pay + rel, tau, eps_ratio, &meta16, &pivot);
+        const uint64_t j = j0 + tid;
+        reinterpret_cast<uint16_t *>(packed + lay.scale)[j] = (uint16_t)meta16;
+        reinterpret_cast<uint16_t *>(packed + lay.zero)[j] = (uint16_t)(meta16 >> 16);
+        packed[lay.pivot + j] = (uint8_t)pivot;
     }
     __syncthreads();
 
-    if (valid) {
-        uint8_t *row = lds + tid * B::STRIDE;
-        float a1, a2;
-        uint32_t d;
-        top2<G, BF16>(row, &a1, &a2, &d);
-        const bool flag = a1 > tau * (a2 + eps_ratio);
-        if (flag && d != 0) {
-            // P_d: swap elements 0 and d inside my LDS row
-            if constexpr (BF16) {
-                uint16_t *r16 = reinterpret_cast<uint16_t *>(row);
-                const uint16_t v0 = r16[0], vd = r16[d];
-                r16[0] = vd; r16[d] = v0;
-            } else {
-                float *r32 = reinterpret_cast<float *>(row);
-                const float v0 = r32[0], vd = r32[d];
-                r32[0] = vd; r32[d] = v0;
-            }
-        }
-        float x[G];
-        read_tile<G, BF16>(row, x);
-        if (flag) {
-            butterfly<G>(x);
+    // the batch's payload is one contiguous span: copy it out unit by unit, coalesced
+    const uint32_t span = 3u * nvalid + total4;
+    U *gdst = reinterpret_cast<U *>(packed + lay.payload) + (3ull * j0 + meta.rank0);
 #pragma unroll
-            for (int k = 0; k < G; ++k) x[k] = x[k] * TileConst<G>::c;
-        }
-        float mn = x[0], mx = x[0];
-#pragma unroll
-        for (int k = 1; k < G; ++k) { mn = __builtin_fminf(mn, x[k]); mx = __builtin_fmaxf(mx, x[k]); }
-        mn = mn + 0.0f;
-        mx = mx + 0.0f;
-
-        // asymmetric quantizer, binary16 metadata rounded outwards
-        const float Lv = (b == 4u) ? 15.0f : 7.0f;
-        const uint32_t z16 = f16_down(mn);
-        const float mnf = f16_widen(z16);
-        const float s = (mx - mnf) / Lv;
-        uint32_t s16 = f16_up(s);
-        if ((s16 & 0x7fffu) == 0) s16 = 0x3c00u;
-        const float sf = f16_widen(s16);
-        const float rcp = 1.0f / sf;
-
-        // codes, four at a time: q0 + m q1 + m^2 q2 + m^3 q3 is an exact integer below 2^16 in fp32
-        const float m1 = (b == 4u) ? 16.0f : 8.0f;
-        const float m2 = m1 * m1, m3 = m2 * m1;
-        uint32_t v[G / 4];
-#pragma unroll
-        for (int g = 0; g < G / 4; ++g) {
-            float q[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                q[i] = __builtin_fminf(__builtin_fmaxf(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f), Lv);
-            const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
-            v[g] = (uint32_t)acc;
-        }
-        // LSB-first bit string of the tile as dwords
-        uint32_t dw[G / 8];
-        if (b == 4u) {
-#pragma unroll
-            for (int i = 0; i < G / 8; ++i) dw[i] = v[2 * i] | (v[2 * i + 1] << 16);
-        } else {
-            // 12-bit groups: eight of them fill three dwords
-#pragma unroll
-            for (int i = 0; i < G / 32; ++i) {
-                const uint32_t *p = v + 8 * i;
-                dw[3 * i + 0] = p[0] | (p[1] << 12) | (p[2] << 24);
-                dw[3 * i + 1] = (p[2] >> 8) | (p[3] << 4) | (p[4] << 16) | (p[5] << 28);
-                dw[3 * i + 2] = (p[5] >> 4) | (p[6] << 8) | (p[7] << 20);
-            }
-#pragma unroll
-            for (int i = 3 * (G / 32); i < G / 8; ++i) dw[i] = 0;
-        }
-        U *dst = pay + rel;
-        constexpr int DPU = G / 32;     // dwords per unit
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (u < 3 || b == 4u) {
-                if constexpr (G == 32) dst[u] = dw[u];
-                else if constexpr (G == 64) dst[u] = make_uint2(dw[2 * u], dw[2 * u + 1]);
-                else dst[u] = make_uint4(dw[4 * u], dw[4 * u + 1], dw[4 * u + 2], dw[4 * u + 3]);
-            }
-        }
-        (void)DPU;
-        reinterpret_cast<uint16_t *>(packed + lay.scale)[j] = (uint16_t)s16;
-        reinterpret_cast<uint16_t *>(packed + lay.zero)[j] = (uint16_t)z16;
-        packed[lay.pivot + j] = flag ? (uint8_t)(0x80u | d) : (uint8_t)0;
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t q = (uint32_t)i * B::TILES + tid;
+        if (q < span) gdst[q] = pay[q];
     }
-    __syncthreads();
-
-    // the batch's payload is one contiguous span: copy it out dword by dword, coalesced
-    const uint32_t span_dw = (G / 32) * (3u * nvalid + total4);
-    uint32_t *gdst = reinterpret_cast<uint32_t *>(packed + lay.payload) + (uint64_t)(G / 32) * (3ull * j0 + rank0);
-    const uint32_t *psrc = reinterpret_cast<const uint32_t *>(pay);
-    for (uint32_t i = tid; i < span_dw; i += B::TILES) gdst[i] = psrc[i];
 }
 
 // ------------------------------------------------------------- K4: decode
 
+// Alg. 1 step 5 for my tile: my 3 or 4 payload units at `src` (LDS) -> codes -> q*s + z -> for
+// transformed tiles the butterfly, 1/sqrt(G) and P_d -> my LDS row in the output type.
+template <int G, bool OUT_BF16>
+__device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, uint32_t b, uint32_t s16, uint32_t z16,
+                                           uint32_t pv, uint8_t *row)
+{
+    using U = typename Unit<G>::type;
+    const float sf = f16_widen(s16), mnf = f16_widen(z16);
+    // my 3 or 4 units (the 4th is read in any case: it stays inside the array)
+    uint32_t dw[G / 8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const U t = src[u];
+        if constexpr (G == 32) dw[u] = t;
+        else if constexpr (G == 64) { dw[2 * u] = t.x; dw[2 * u + 1] = t.y; }
+        else { dw[4 * u] = t.x; dw[4 * u + 1] = t.y; dw[4 * u + 2] = t.z; dw[4 * u + 3] = t.w; }
+    }
+    // bring three-bit codes onto nibble boundaries: 24 bits (8 codes) -> 32 bits
+    uint32_t nib[G / 8];
+    if (b == 4u) {
+#pragma unroll
+        for (int i = 0; i < G / 8; ++i) nib[i] = dw[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < G / 8; ++i) {
+            // codes 8i .. 8i+7 occupy bits [24i, 24i+24) of the string
+            const int lo = (24 * i) >> 5, sh = (24 * i) & 31;
+            uint32_t t = dw[lo] >> sh;
+            if (sh > 8) t |= dw[lo + 1] << (32 - sh);
+            t &= 0x00ffffffu;
+            t = (t & 0x00000fffu) | ((t & 0x00fff000u) << 4);
+            t = (t & 0x003f003fu) | ((t & 0x0fc00fc0u) << 2);
+            t = (t & 0x07070707u) | ((t & 0x38383838u) << 1);
+            nib[i] = t;
+        }
+    }
+    // de-quantize: even codes sit in the low nibbles of the bytes, odd codes in the high nibbles
+    // (scaled by 16, undone exactly by a scale of sf/16)
+    const float sf16 = sf * 0.0625f;
+    float x[G];
+#pragma unroll
+    for (int i = 0; i < G / 8; ++i) {
+        const uint32_t lo = nib[i] & 0x0f0f0f0fu, hi = nib[i] & 0xf0f0f0f0u;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            x[8 * i + 2 * c] = __builtin_fmaf((float)((lo >> (8 * c)) & 0xffu), sf, mnf);
+            x[8 * i + 2 * c + 1] = __builtin_fmaf((float)((hi >> (8 * c)) & 0xffu), sf16, mnf);
+        }
+    }
+    if (pv & 0x80u) {
+        butterfly<G>(x);
+#pragma unroll
+        for (int k = 0; k < G; ++k) x[k] = x[k] * TileConst<G>::c;
+    }
+    // my tile into its LDS row, narrowed to the output type
+    if constexpr (OUT_BF16) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float floatx2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int c = 0; c < G / 8; ++c) {
+            uint32_t ws[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const floatx2 pr = {x[8 * c + 2 * i], x[8 * c + 2 * i + 1]};
+                ws[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+            }
+            *reinterpret_cast<uint4 *>(row + c * 16) = make_uint4(ws[0], ws[1], ws[2], ws[3]);
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < G / 4; ++c)
+            *reinterpret_cast<float4 *>(row + c * 16) = make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
+    }
+    const uint32_t d = pv & 0x7fu;
+    if ((pv & 0x80u) && d != 0) {
+        // undo P_d inside my row
+        if constexpr (OUT_BF16) {
+            uint16_t *r16 = reinterpret_cast<uint16_t *>(row);
+            const uint16_t v0 = r16[0], vd = r16[d];
+            r16[0] = vd; r16[d] = v0;
+        } else {
+            float *r32 = reinterpret_cast<float *>(row);
+            const float v0 = r32[0], vd = r32[d];
+            r32[0] = vd; r32[d] = v0;
+        }
+    }
+}
+
+// Persistent workgroups over the full batches, software-pipelined: while batch i is decoded, the payload
+// span, bit map words and per-tile metadata of batch i+1 are in flight; the stores of batch i are issued
+// at the end of its iteration and drain during the next one.  The fast loop has no per-thread conditions
+// on global memory operations, so every wait counts exactly the operations it must leave outstanding.
+// The only two-step dependency -- the rank-table entry that locates a batch's payload -- is taken out of
+// the loop: the entries of all batches of this workgroup are read into LDS up front.
+// The ragged last batch is handled after the loop by one workgroup.
 template <int G, bool OUT_BF16>
 __global__ __launch_bounds__((Batch<G, OUT_BF16 ? 2 : 4>::TILES))
 void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout lay, uint32_t T)
@@ -355,130 +546,91 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     constexpr int ES = OUT_BF16 ? 2 : 4;
     using B = Batch<G, ES>;
     using U = typename Unit<G>::type;
+    using Meta = BatchMeta<B::TILES>;
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
     __shared__ __attribute__((aligned(16))) U pay[B::TILES * 4];
+    __shared__ uint32_t rank_lds[B::TILES];
     const int tid = threadIdx.x;
-    const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
-    const uint32_t left = (uint32_t)(T - j0);
-    const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
-    const uint64_t j = j0 + tid;
-    const bool valid = (uint32_t)tid < nvalid;
-
-    const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap);
+    const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
+    const uint16_t *scale = reinterpret_cast<const uint16_t *>(packed + lay.scale);
+    const uint16_t *zero = reinterpret_cast<const uint16_t *>(packed + lay.zero);
+    const uint8_t *pivot = packed + lay.pivot;
     const uint32_t *ranks = reinterpret_cast<const uint32_t *>(packed + lay.ranks);
-    const uint32_t rank0 = ranks[j0 >> 6];
-    uint32_t b = 3, rel = 0, total4 = 0;
-#pragma unroll
-    for (int w = 0; w < (B::TILES + 63) / 64; ++w) {
-        const uint64_t jw = (j0 >> 6) + w;
-        const uint64_t word = jw * 64 < T ? bitmap[jw] : 0ull;
-        if (w == (tid >> 6)) {
-            const uint32_t bit = (uint32_t)tid & 63u;
-            b = 3u + (uint32_t)((word >> bit) & 1ull);
-            rel = 3u * (uint32_t)tid + total4 + (uint32_t)__popcll(word & ((1ull << bit) - 1ull));
-        }
-        total4 += (uint32_t)__popcll(word);
-    }
-
-    // stage the batch's payload span
-    const uint32_t span_dw = (G / 32) * (3u * nvalid + total4);
-    const uint32_t *gsrc = reinterpret_cast<const uint32_t *>(packed + lay.payload) + (uint64_t)(G / 32) * (3ull * j0 + rank0);
-    uint32_t *pdst = reinterpret_cast<uint32_t *>(pay);
-    for (uint32_t i = tid; i < span_dw; i += B::TILES) pdst[i] = gsrc[i];
-
-    uint32_t s16 = 0, z16 = 0, pv = 0;
-    if (valid) {
-        s16 = reinterpret_cast<const uint16_t *>(packed + lay.scale)[j];
-        z16 = reinterpret_cast<const uint16_t *>(packed + lay.zero)[j];
-        pv = packed[lay.pivot + j];
-    }
-    __syncthreads();
-
+    const U *payload = reinterpret_cast<const U *>(packed + lay.payload);
+    const uint64_t last_unit = (lay.total - lay.payload) / sizeof(U) - 1;    // last unit of the stream
     uint8_t *row = lds + tid * B::STRIDE;
-    if (valid) {
-        const float sf = f16_widen(s16), mnf = f16_widen(z16);
-        // my 3 or 4 units (the 4th is read in any case: it stays inside the array)
-        uint32_t dw[G / 8];
-        const U *src = pay + rel;
+    uint32_t lane_zero = 0;
+    asm volatile("" : "+v"(lane_zero));
+    const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap) + lane_zero;
+
+    // rank-table entries of TILES consecutive batches of this workgroup, starting at its iteration `first`
+    auto load_rank_window = [&](uint32_t first) {
+        const uint64_t bb = (uint64_t)blockIdx.x + ((uint64_t)first + tid) * gridDim.x;
+        if (bb < nfull) rank_lds[tid] = ranks[bb * (B::TILES / 64)];
+        __syncthreads();
+    };
+    load_rank_window(0);
+    uint32_t wbase = 0;
+
+    Meta m;            // bit map words of the batch whose loads are in flight / have just arrived
+    U pre[4];
+    uint32_t s16 = 0, z16 = 0, pv = 0;
+    // issue the loads of full batch `batch`, whose rank-table entry is slot `slot` of the LDS window
+    auto fetch = [&](uint32_t batch, uint32_t slot) {
+        const uint64_t j0 = (uint64_t)batch * B::TILES;
+        m.rank0 = rank_lds[slot];
+        const uint64_t base = 3ull * j0 + m.rank0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const U t = src[u];
-            if constexpr (G == 32) dw[u] = t;
-            else if constexpr (G == 64) { dw[2 * u] = t.x; dw[2 * u + 1] = t.y; }
-            else { dw[4 * u] = t.x; dw[4 * u + 1] = t.y; dw[4 * u + 2] = t.z; dw[4 * u + 3] = t.w; }
-        }
-        // bring three-bit codes onto nibble boundaries: 24 bits (8 codes) -> 32 bits
-        uint32_t nib[G / 8];
-        if (b == 4u) {
+        for (int i = 0; i < 3; ++i) pre[i] = payload[base + (uint32_t)i * B::TILES + tid];
+        // the fourth unit may lie beyond the batch's span (it is then not used): keep it inside the stream
+        const uint64_t q3 = base + 3u * (uint32_t)B::TILES + (uint32_t)tid;
+        pre[3] = payload[q3 < last_unit ? q3 : last_unit];
 #pragma unroll
-            for (int i = 0; i < G / 8; ++i) nib[i] = dw[i];
-        } else {
+        for (int w = 0; w < Meta::WORDS; ++w) m.word[w] = bitmap[(j0 >> 6) + w];
+        s16 = scale[j0 + tid];
+        z16 = zero[j0 + tid];
+        pv = pivot[j0 + tid];
+    };
+
+    uint32_t batch = blockIdx.x, it = 0;
+    if (batch < nfull) fetch(batch, 0);
+    for (; batch < nfull; batch += gridDim.x, ++it) {
+        uint32_t b, rel, total4;
+        tile_pos<B::TILES>(m, tid, &b, &rel, &total4);
 #pragma unroll
-            for (int i = 0; i < G / 8; ++i) {
-                // codes 8i .. 8i+7 occupy bits [24i, 24i+24) of the string
-                const int lo = (24 * i) >> 5, sh = (24 * i) & 31;
-                uint32_t t = dw[lo] >> sh;
-                if (sh > 8) t |= dw[lo + 1] << (32 - sh);
-                t &= 0x00ffffffu;
-                t = (t & 0x00000fffu) | ((t & 0x00fff000u) << 4);
-                t = (t & 0x003f003fu) | ((t & 0x0fc00fc0u) << 2);
-                t = (t & 0x07070707u) | ((t & 0x38383838u) << 1);
-                nib[i] = t;
+        for (int i = 0; i < 4; ++i) pay[(uint32_t)i * B::TILES + tid] = pre[i];
+        const uint32_t my_s16 = s16, my_z16 = z16, my_pv = pv;
+        __syncthreads();
+
+        const uint32_t next = batch + gridDim.x;
+        if (next < nfull) {
+            if (it + 1 - wbase == (uint32_t)B::TILES) {      // once every TILES iterations
+                __syncthreads();
+                wbase = it + 1;
+                load_rank_window(wbase);
             }
+            fetch(next, it + 1 - wbase);
         }
-        // de-quantize: even codes sit in the low nibbles of the bytes, odd codes in the high nibbles
-        // (scaled by 16, undone exactly by a scale of sf/16)
-        const float sf16 = sf * 0.0625f;
-        float x[G];
-#pragma unroll
-        for (int i = 0; i < G / 8; ++i) {
-            const uint32_t lo = nib[i] & 0x0f0f0f0fu, hi = nib[i] & 0xf0f0f0f0u;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                x[8 * i + 2 * c] = __builtin_fmaf((float)((lo >> (8 * c)) & 0xffu), sf, mnf);
-                x[8 * i + 2 * c + 1] = __builtin_fmaf((float)((hi >> (8 * c)) & 0xffu), sf16, mnf);
-            }
-        }
-        if (pv & 0x80u) {
-            butterfly<G>(x);
-#pragma unroll
-            for (int k = 0; k < G; ++k) x[k] = x[k] * TileConst<G>::c;
-        }
-        // my tile into its LDS row, narrowed to the output type
-        if constexpr (OUT_BF16) {
-            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-            typedef float floatx2 __attribute__((ext_vector_type(2)));
-#pragma unroll
-            for (int c = 0; c < G / 8; ++c) {
-                uint32_t ws[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const floatx2 pr = {x[8 * c + 2 * i], x[8 * c + 2 * i + 1]};
-                    ws[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-                }
-                *reinterpret_cast<uint4 *>(row + c * 16) = make_uint4(ws[0], ws[1], ws[2], ws[3]);
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < G / 4; ++c)
-                *reinterpret_cast<float4 *>(row + c * 16) = make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
-        }
-        const uint32_t d = pv & 0x7fu;
-        if ((pv & 0x80u) && d != 0) {
-            // undo P_d inside my row
-            if constexpr (OUT_BF16) {
-                uint16_t *r16 = reinterpret_cast<uint16_t *>(row);
-                const uint16_t v0 = r16[0], vd = r16[d];
-                r16[0] = vd; r16[d] = v0;
-            } else {
-                float *r32 = reinterpret_cast<float *>(row);
-                const float v0 = r32[0], vd = r32[d];
-                r32[0] = vd; r32[d] = v0;
-            }
-        }
+        decode_row<G, OUT_BF16>(pay + rel, b, my_s16, my_z16, my_pv, row);
+        __syncthreads();
+        stage_out<G, ES, true>(out, (uint64_t)batch * B::TILES, B::TILES, lds);
     }
-    __syncthreads();
-    stage_out<G, ES>(out, j0, nvalid, lds);
+
+    if (tail != 0 && blockIdx.x == nfull % gridDim.x) {
+        __syncthreads();
+        const uint64_t j0 = (uint64_t)nfull * B::TILES;
+        load_meta<B::TILES>(packed, lay, j0, T, 0u, m);
+        uint32_t b, rel, total4;
+        tile_pos<B::TILES>(m, tid, &b, &rel, &total4);
+        const uint32_t span = 3u * tail + total4;
+        const U *gsrc = payload + (3ull * j0 + m.rank0);
+        for (uint32_t q = tid; q < span; q += B::TILES) pay[q] = gsrc[q];
+        __syncthreads();
+        if ((uint32_t)tid < tail)
+            decode_row<G, OUT_BF16>(pay + rel, b, scale[j0 + tid], zero[j0 + tid], pivot[j0 + tid], row);
+        __syncthreads();
+        stage_out<G, ES, false>(out, j0, tail, lds);
+    }
 }
 
 }  // namespace tahq
