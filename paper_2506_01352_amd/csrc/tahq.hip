@@ -34,26 +34,37 @@ inline void dispatch(uint32_t G, bool bf16, Args... args)
     else { if (bf16) F<128, true>::run(args...); else F<128, false>::run(args...); }
 }
 
-// Persistent launch: as many workgroups as fit on the device at once (or fewer, if there are fewer batches).
+// Grid of a persistent kernel: four times the workgroups that fit on the device at once (or fewer, if there
+// are fewer batches).  Every workgroup still pipelines a few batches, and the hardware dispatcher evens
+// out the load; a grid of exactly the resident count measured up to 30% slower.
 inline uint32_t resident_blocks(const void *kernel, int threads)
 {
     int dev = 0, cus = 256, per_cu = 1;
     if (hipGetDevice(&dev) != hipSuccess) dev = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu <= 0) per_cu = 1;
-    return (uint32_t)cus * (uint32_t)per_cu;
+    return 4u * (uint32_t)cus * (uint32_t)per_cu;
 }
 
 template <int G, bool BF16>
 struct LaunchEntropy {
-    static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, hipStream_t st)
+    // hist0 != nullptr: also build the selection's first-digit histogram (units must be whole batches)
+    static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, uint32_t *hist0,
+                    uint64_t n_per_unit, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
         static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_entropy<G, BF16>), B::TILES);
+        const uint32_t unit_batches = hist0 ? (uint32_t)(n_per_unit / B::TILES) : 1u;
         hipLaunchKernelGGL((k_entropy<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, d_in, d_H, T,
-                           eps_l1, eps_log);
+                           eps_l1, eps_log, hist0, unit_batches, 3u * kHistBins);
     }
+    static bool can_fuse_histogram(uint64_t n_per_unit) { return n_per_unit % Batch<G, BF16 ? 2 : 4>::TILES == 0; }
+};
+
+template <int G, bool BF16>
+struct CanFuse {
+    static void run(uint64_t n_per_unit, bool *out) { *out = LaunchEntropy<G, BF16>::can_fuse_histogram(n_per_unit); }
 };
 
 template <int G, bool BF16>
@@ -78,9 +89,15 @@ struct LaunchDecode {
     }
 };
 
-void launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, hipStream_t st)
+// Returns true if the first-digit histogram was built along the way.
+bool launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, uint32_t *hist0,
+                    hipStream_t st)
 {
-    dispatch<LaunchEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_H, (uint32_t)s.T, cfg->eps_l1, cfg->eps_log, st);
+    bool fuse = false;
+    if (hist0) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fuse);
+    dispatch<LaunchEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_H, (uint32_t)s.T, cfg->eps_l1, cfg->eps_log,
+                            fuse ? hist0 : (uint32_t *)nullptr, s.n, st);
+    return fuse;
 }
 
 }  // namespace
@@ -136,7 +153,7 @@ tahq_status tahq_tile_entropy(const tahq_config *cfg, const void *d_in, float *d
     if (rc != TAHQ_OK) return rc;
     if (!d_in || !d_entropy) return TAHQ_ERR_NULL;
     if (misaligned(d_in) || misaligned(d_entropy)) return TAHQ_ERR_MISALIGNED;
-    launch_entropy(s, cfg, d_in, d_entropy, (hipStream_t)stream);
+    launch_entropy(s, cfg, d_in, d_entropy, nullptr, (hipStream_t)stream);
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
 
@@ -192,13 +209,17 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
         uint32_t *state = reinterpret_cast<uint32_t *>(wsb + ws.state);
         uint32_t *seg = reinterpret_cast<uint32_t *>(wsb + ws.seg);
         uint8_t *sel = wsb + ws.sel;
-        if (phases & TAHQ_PHASE_ENTROPY) launch_entropy(s, cfg, d_in, H, st);
+        // the entropy kernel builds the first-digit histogram itself when units are whole batches
+        bool fused = false;
+        dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
+        if (phases & TAHQ_PHASE_ENTROPY) launch_entropy(s, cfg, d_in, H, hist, st);
         if (phases & TAHQ_PHASE_SELECT) {
             // few, fat blocks: every block flushes up to 2048 bins with global atomics
             uint32_t hb = (uint32_t)((s.n + 16383) / 16384);
             if (hb > 64) hb = 64;
             const uint32_t n32 = (uint32_t)s.n, k32 = (uint32_t)s.k;
-            hipLaunchKernelGGL((k_radix_pass<0, 8>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
+            if (!fused)
+                hipLaunchKernelGGL((k_radix_pass<0, 8>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
             hipLaunchKernelGGL((k_radix_pass<1, 0>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
             hipLaunchKernelGGL((k_radix_pass<2, 0>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
             const uint32_t sb = (ws.nseg + 3) / 4;

@@ -23,7 +23,7 @@ struct Layout {
     uint64_t bitmap, ranks, pivot, scale, zero, payload, total;
 };
 
-constexpr uint32_t kSegTiles = 2048;     // tiles one wavefront handles in the selection kernels
+constexpr uint32_t kSegTiles = 1024;     // tiles one wavefront handles in the selection kernels
 constexpr uint32_t kHistBins = 2048;
 
 struct Workspace {

@@ -2,7 +2,8 @@
 // 4 bits, ties going to the lower tile index.  Exact, deterministic, no sort:
 //
 //   * entropies map to order-preserving 32-bit keys;
-//   * three histogram passes (11 + 11 + 10 bits, from the top) find the k-th largest key K*
+//   * three histogram passes (10 + 11 + 11 bits, from the top; the first one is normally folded into
+//     the entropy kernel) find the k-th largest key K*
 //     and how many tiles equal to K* are still wanted (`take`);
 //   * per segment of tiles, counts of keys == K* and > K* ; their prefix sums give every tile
 //     its place among the equal keys (index order) and every 64-tile group its rank-table entry.
@@ -12,14 +13,9 @@
 // recomputed by every block from a few KB of global data.
 #pragma once
 #include "tahq_common.hpp"
+#include "tahq_stream_kernels.hpp"
 
 namespace tahq {
-
-__device__ __forceinline__ uint32_t order_key(float h)
-{
-    const uint32_t u = __float_as_uint(h);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
 
 // Inclusive scan over the 64 lanes of a wavefront.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
@@ -36,24 +32,26 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
 // selection state of one ranking unit (uint32[8] in the workspace)
 enum { ST_BIN0 = 0, ST_BIN1 = 1, ST_BIN2 = 2, ST_KREM0 = 3, ST_KREM1 = 4, ST_KEY = 5, ST_TAKE = 6 };
 
-// Which bin of a 2048-bin histogram holds the `want`-th largest key (bins counted from the top),
-// and how many keys are still wanted inside that bin.  Run by one full wavefront; lane l owns the
-// 32 bins 2047-32l .. 2016-32l.  Result is returned in every lane.
+// Which bin of a BINS-bin histogram holds the `want`-th largest key (bins counted from the top), and how
+// many keys are still wanted inside that bin.  Run by one full wavefront; lane l owns the BINS/64 bins
+// just below BINS - l*BINS/64.  Result is returned in every lane.
+template <int BINS>
 __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint32_t want, uint32_t *bin,
                                          uint32_t *rem)
 {
+    constexpr int PER = BINS / 64;
     const int lane = threadIdx.x & 63;
-    uint32_t c[32], mine = 0;
+    uint32_t c[PER], mine = 0;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) { c[i] = hist[kHistBins - 1 - (lane * 32 + i)]; mine += c[i]; }
-    uint32_t above = wave_incl_scan(mine) - mine;      // keys in bins above my 32
+    for (int i = 0; i < PER; ++i) { c[i] = hist[BINS - 1 - (lane * PER + i)]; mine += c[i]; }
+    uint32_t above = wave_incl_scan(mine) - mine;      // keys in bins above mine
     uint32_t found_bin = 0, found_rem = 0;
     bool found = false;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
+    for (int i = 0; i < PER; ++i) {
         if (!found && above < want && want <= above + c[i]) {
             found = true;
-            found_bin = kHistBins - 1 - (lane * 32 + i);
+            found_bin = BINS - 1 - (lane * PER + i);
             found_rem = want - above;
         }
         above += c[i];
@@ -65,16 +63,18 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
     *rem = (uint32_t)__shfl((int)found_rem, src, 64);
 }
 
-// One radix pass.  Digits: pass 0 = key bits 31..21, pass 1 = bits 20..10, pass 2 = bits 9..0.
-// Pass p > 0 first derives, from the histogram of pass p-1, the bin chosen there (every block does
-// this; block 0 of the unit also records it in `state`), then histograms digit p of the keys whose
-// higher digits match.  PEEL > 0 aggregates equal digits inside a wavefront before touching LDS
-// (pass 0 sees only a handful of distinct digits, which would serialize the LDS atomics).
+// One radix pass.  Digits: pass 0 = key bits 31..22 (1024 bins), pass 1 = bits 21..11, pass 2 = bits 10..0
+// (2048 bins each).  Pass p > 0 first derives, from the histogram of pass p-1, the bin chosen there (every
+// block does this; block 0 of the unit also records it in `state`), then histograms digit p of the keys
+// whose higher digits match.  Pass 0 runs as a kernel of its own only when the entropy kernel could not
+// build its histogram; PEEL > 0 then aggregates equal digits inside a wavefront before touching LDS
+// (it sees only a handful of distinct digits, which would serialize the LDS atomics).
 template <int PASS, int PEEL>
 __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H, uint32_t n, uint32_t k,
                                                     uint32_t *__restrict__ hist, uint32_t *__restrict__ state)
 {
-    __shared__ uint32_t lh[kHistBins];
+    constexpr int BINS = PASS == 0 ? kDigit0Bins : (int)kHistBins;
+    __shared__ uint32_t lh[BINS];
     __shared__ uint32_t chosen[2];
     const uint32_t u = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -82,14 +82,15 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
     uint32_t *ust = state + (uint64_t)u * 8;
     const float *uH = H + (uint64_t)u * n;
 
-    for (int i = tid; i < (int)kHistBins; i += 256) lh[i] = 0;
+    for (int i = tid; i < BINS; i += 256) lh[i] = 0;
 
     uint32_t want_hi = 0;
     if (PASS > 0) {
         if (tid < 64) {
             const uint32_t want = PASS == 1 ? k : ust[ST_KREM0];
             uint32_t bin, rem;
-            pick_bin(uh - kHistBins, want, &bin, &rem);
+            if (PASS == 1) pick_bin<kDigit0Bins>(uh - kHistBins, want, &bin, &rem);
+            else pick_bin<kHistBins>(uh - kHistBins, want, &bin, &rem);
             if (lane == 0) {
                 chosen[0] = bin;
                 chosen[1] = rem;
@@ -102,23 +103,24 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
         __syncthreads();
     }
 
-    constexpr int shift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
-    constexpr uint32_t mask = PASS == 2 ? 1023u : 2047u;
-    constexpr int hi_shift = PASS == 1 ? 21 : 10;
+    constexpr int shift = PASS == 0 ? 22 : (PASS == 1 ? 11 : 0);
+    constexpr uint32_t mask = PASS == 0 ? 1023u : 2047u;
+    constexpr int hi_shift = PASS == 1 ? 22 : 11;
 
-    // every thread walks the unit's keys in steps of the grid; four loads are in flight at a time
+    // every thread walks the unit's keys in steps of the grid; sixteen loads are in flight at a time
+    constexpr int R = 16;
     const uint64_t stride = (uint64_t)gridDim.x * 256;
-    for (uint64_t base = (uint64_t)blockIdx.x * 256 + tid; base < n; base += 4 * stride) {
-        uint32_t key[4];
-        bool ok[4];
+    for (uint64_t base = (uint64_t)blockIdx.x * 256 + tid; base < n; base += R * stride) {
+        uint32_t key[R];
+        bool ok[R];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < R; ++r) {
             const uint64_t i = base + r * stride;
             ok[r] = i < n;
             key[r] = ok[r] ? order_key(uH[i]) : 0u;
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < R; ++r) {
             bool active = ok[r] && (PASS == 0 || (key[r] >> hi_shift) == want_hi);
             const uint32_t bin = (key[r] >> shift) & mask;
 #pragma unroll 1
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
         }
     }
     __syncthreads();
-    for (int i = tid; i < (int)kHistBins; i += 256)
+    for (int i = tid; i < BINS; i += 256)
         if (lh[i]) atomicAdd(&uh[i], lh[i]);
 }
 
@@ -152,8 +154,8 @@ __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, 
     uint32_t *ust = state + (uint64_t)u * 8;
     if (tid < 64) {
         uint32_t bin, rem;
-        pick_bin(hist + ((uint64_t)u * 3 + 2) * kHistBins, ust[ST_KREM1], &bin, &rem);
-        const uint32_t key = (ust[ST_BIN0] << 21) | (ust[ST_BIN1] << 10) | bin;
+        pick_bin<kHistBins>(hist + ((uint64_t)u * 3 + 2) * kHistBins, ust[ST_KREM1], &bin, &rem);
+        const uint32_t key = (ust[ST_BIN0] << 22) | (ust[ST_BIN1] << 11) | bin;
         if (lane == 0) {
             chosen[0] = key;
             chosen[1] = rem;

@@ -144,41 +144,79 @@ __device__ __forceinline__ float entropy_of_row(const uint8_t *row, float eps_l1
     return 0.0f - tree_sum<G>(a);
 }
 
-// Persistent workgroups: workgroup w handles the full batches w, w + gridDim.x, ...  The next batch's
-// loads are issued before the current batch is processed, and a batch's result is stored one iteration
-// later, just before those loads, so that no wait for loads ever has a younger store in front of it.
+// Order-preserving 32-bit key of an entropy (larger entropy -> larger key).
+__device__ __forceinline__ uint32_t order_key(float h)
+{
+    const uint32_t u = __float_as_uint(h);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kDigit0Bits = 10;                  // first radix digit of the selection: key bits 31..22
+constexpr int kDigit0Bins = 1 << kDigit0Bits;
+
+// Persistent workgroups: workgroup w handles a contiguous run of full batches.  The next batch's loads
+// are issued before the current batch is processed, and a batch's result is stored one iteration later,
+// just before those loads, so that no wait for loads ever has a younger store in front of it.
 // The ragged last batch (T not a multiple of TILES) is handled after the loop by one workgroup.
+//
+// If `hist0` is given, the kernel also builds the first-digit histogram of the selection (Sec. 3.2,
+// top-p%): per ranking unit of `unit_batches` batches, counts of the keys' top 10 bits, accumulated in
+// LDS and flushed with global atomics when the workgroup moves to another unit and at its end.  This
+// needs units that are whole numbers of batches (the caller checks; otherwise it passes no histogram).
 template <int G, bool BF16>
 __global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
-void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, float eps_l1, float eps_log)
+void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, float eps_l1, float eps_log,
+               uint32_t *__restrict__ hist0, uint32_t unit_batches, uint32_t hist_stride)
 {
     constexpr int ES = BF16 ? 2 : 4;
     using B = Batch<G, ES>;
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
+    __shared__ uint32_t lh[kDigit0Bins];
     const int tid = threadIdx.x;
     const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
     const uint8_t *row = lds + tid * B::STRIDE;
+    const uint32_t per = (nfull + gridDim.x - 1) / gridDim.x;
+    const uint32_t first = blockIdx.x * per;
+    const uint32_t last = first + per < nfull ? first + per : nfull;      // my batches: [first, last)
+
+    if (hist0) {
+        for (int i = tid; i < kDigit0Bins; i += B::TILES) lh[i] = 0;
+    }
+    auto flush = [&](uint32_t unit) {
+        __syncthreads();
+        for (int i = tid; i < kDigit0Bins; i += B::TILES) {
+            const uint32_t c = lh[i];
+            if (c) { atomicAdd(&hist0[(uint64_t)unit * hist_stride + i], c); lh[i] = 0; }
+        }
+        __syncthreads();
+    };
 
     uint4 v[B::CHUNKS];
-    uint32_t batch = blockIdx.x;
-    if (batch < nfull) load_batch<G, ES, true>(in, (uint64_t)batch * B::TILES, B::TILES, v);
+    if (first < last) load_batch<G, ES, true>(in, (uint64_t)first * B::TILES, B::TILES, v);
     float h_prev = 0.0f;
     uint64_t j_prev = 0;
     bool have_prev = false;
-    for (; batch < nfull; batch += gridDim.x) {
+    uint32_t cur_unit = hist0 && first < last ? first / unit_batches : 0u;
+    for (uint32_t batch = first; batch < last; ++batch) {
+        if (hist0) {
+            const uint32_t unit = batch / unit_batches;
+            if (unit != cur_unit) { flush(cur_unit); cur_unit = unit; }
+        }
         store_batch<G, ES, true>(v, B::TILES, lds);
         __syncthreads();
         if (have_prev) H[j_prev] = h_prev;
-        const uint32_t next = batch + gridDim.x;
-        if (next < nfull) load_batch<G, ES, true>(in, (uint64_t)next * B::TILES, B::TILES, v);
+        if (batch + 1 < last) load_batch<G, ES, true>(in, (uint64_t)(batch + 1) * B::TILES, B::TILES, v);
         h_prev = entropy_of_row<G, BF16>(row, eps_l1, eps_log);
+        if (hist0) atomicAdd(&lh[order_key(h_prev) >> (32 - kDigit0Bits)], 1u);
         j_prev = (uint64_t)batch * B::TILES + tid;
         have_prev = true;
         __syncthreads();
     }
     if (have_prev) H[j_prev] = h_prev;
+    if (hist0 && first < last) flush(cur_unit);
 
-    if (tail != 0 && blockIdx.x == nfull % gridDim.x) {
+    if (tail != 0 && blockIdx.x == gridDim.x - 1) {
+        // never combined with a histogram: a ragged batch means units are not whole batches
         const uint64_t j0 = (uint64_t)nfull * B::TILES;
         load_batch<G, ES, false>(in, j0, tail, v);
         store_batch<G, ES, false>(v, tail, lds);
