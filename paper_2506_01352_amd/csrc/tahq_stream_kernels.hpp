@@ -340,20 +340,30 @@ __device__ __forceinline__ void tile_pos(const BatchMeta<TILES> &m, int tid, uin
     *b = bb; *rel = rr; *total4 = tot;
 }
 
-// Everything the encoder does to my tile once its width b is known: Eq. 3 (outlier test), P_d and
-// Eq. 4 on outlier tiles, range, quantizer parameters, codes, and the tile's LSB-first bit string
-// written as b units at `dst` (LDS).  Returns scale | zero << 16 and the pivot byte.
-template <int G, bool BF16>
-__device__ __forceinline__ void quantize_row(uint8_t *row, uint32_t b, typename Unit<G>::type *dst, float tau,
-                                             float eps_ratio, uint32_t *meta16, uint32_t *pivot)
+// Three-input float min / max in one instruction each (no NaN canonicalisation around them).
+__device__ __forceinline__ float fmin3(float a, float b, float c)
 {
-    using U = typename Unit<G>::type;
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float fmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Eq. 3 for the tile in `row`: outlier flag and pivot index; for an outlier tile with d != 0 the pivot
+// swap P_d is applied to the LDS row on the spot.  Returns the pivot byte (bit 7 = flag, bits 0..6 = d).
+template <int G, bool BF16>
+__device__ __forceinline__ uint32_t analyse_row(uint8_t *row, float tau, float eps_ratio)
+{
     float a1, a2;
     uint32_t d;
     top2<G, BF16>(row, &a1, &a2, &d);
     const bool flag = a1 > tau * (a2 + eps_ratio);
     if (flag && d != 0) {
-        // P_d: swap elements 0 and d inside my LDS row
         if constexpr (BF16) {
             uint16_t *r16 = reinterpret_cast<uint16_t *>(row);
             const uint16_t v0 = r16[0], vd = r16[d];
@@ -364,6 +374,16 @@ __device__ __forceinline__ void quantize_row(uint8_t *row, uint32_t b, typename 
             r32[0] = vd; r32[d] = v0;
         }
     }
+    return flag ? (0x80u | d) : 0u;
+}
+
+// The rest of the encoder for one tile whose row already carries P_d: Eq. 4 on outlier tiles, range,
+// quantizer parameters, codes, and the tile's LSB-first bit string written as b units at `dst` (LDS).
+// Returns scale | zero << 16.
+template <int G, bool BF16>
+__device__ __forceinline__ uint32_t quantize_row(const uint8_t *row, bool flag, uint32_t b,
+                                                 typename Unit<G>::type *dst)
+{
     float x[G];
     read_tile<G, BF16>(row, x);
     if (flag) {
@@ -371,11 +391,11 @@ __device__ __forceinline__ void quantize_row(uint8_t *row, uint32_t b, typename 
 #pragma unroll
         for (int k = 0; k < G; ++k) x[k] = x[k] * TileConst<G>::c;
     }
-    float mn = x[0], mx = x[0];
+    float mn = fmin3(x[0], x[1], x[2]), mx = fmax3(x[0], x[1], x[2]);
 #pragma unroll
-    for (int k = 1; k < G; ++k) { mn = __builtin_fminf(mn, x[k]); mx = __builtin_fmaxf(mx, x[k]); }
-    mn = mn + 0.0f;
-    mx = mx + 0.0f;
+    for (int k = 3; k + 1 < G; k += 2) { mn = fmin3(mn, x[k], x[k + 1]); mx = fmax3(mx, x[k], x[k + 1]); }
+    mn = __builtin_fminf(mn, x[G - 1]) + 0.0f;
+    mx = __builtin_fmaxf(mx, x[G - 1]) + 0.0f;
 
     // asymmetric quantizer, binary16 metadata rounded outwards
     const float Lv = (b == 4u) ? 15.0f : 7.0f;
@@ -425,14 +445,15 @@ __device__ __forceinline__ void quantize_row(uint8_t *row, uint32_t b, typename 
             else dst[u] = make_uint4(dw[4 * u], dw[4 * u + 1], dw[4 * u + 2], dw[4 * u + 3]);
         }
     }
-    (void)sizeof(U);
-    *meta16 = s16 | (z16 << 16);
-    *pivot = flag ? (0x80u | d) : 0u;
+    return s16 | (z16 << 16);
 }
 
-// One workgroup per batch of TILES tiles.  (This kernel is bound by vector-ALU issue; keeping it
-// non-persistent keeps its register count down, and its loads are covered by the other resident
-// workgroups.)
+// One workgroup per batch of TILES tiles, in two rounds.  Round 1: lane i examines tile i (Eq. 3, pivot
+// swap in LDS).  The tiles are then regrouped by class -- (plain | transformed) x (3 | 4 bit) -- so that in
+// round 2, where lane p takes the p-th tile in class order, most wavefronts hold a single class: the
+// Hadamard butterfly runs only in the wavefronts that hold transformed tiles, and the 3-/4-bit packing
+// paths rarely both run.  (This kernel is bound by vector-ALU issue; its loads are covered by the
+// other resident workgroups.)
 template <int G, bool BF16>
 __global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
 void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Layout lay, uint32_t T, float tau,
@@ -441,9 +462,13 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     constexpr int ES = BF16 ? 2 : 4;
     using B = Batch<G, ES>;
     using U = typename Unit<G>::type;
+    constexpr int WAVES = (B::TILES + 63) / 64;
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
     __shared__ __attribute__((aligned(16))) U pay[B::TILES * 4];
-    const int tid = threadIdx.x;
+    __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == 4) << 8 | rel << 9
+    __shared__ uint16_t order[B::TILES];         // tiles in class order
+    __shared__ uint32_t class_count[WAVES][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
     const uint32_t left = (uint32_t)(T - j0);
     const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
@@ -460,13 +485,43 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     tile_pos<B::TILES>(meta, tid, &b, &rel, &total4);
     __syncthreads();
 
-    if ((uint32_t)tid < nvalid) {
-        uint32_t meta16, pivot;
-        quantize_row<G, BF16>(lds + tid * B::STRIDE, b, pay + rel, tau, eps_ratio, &meta16, &pivot);
-        const uint64_t j = j0 + tid;
+    // round 1: my own tile
+    const bool valid = (uint32_t)tid < nvalid;
+    uint32_t cls = 4;                            // tiles past the end sort last
+    if (valid) {
+        const uint32_t pv = analyse_row<G, BF16>(lds + tid * B::STRIDE, tau, eps_ratio);
+        info[tid] = pv | ((b == 4u) ? 0x100u : 0u) | (rel << 9);
+        cls = ((pv >> 7) << 1) | (b == 4u ? 1u : 0u);
+    }
+    uint32_t rank_in_wave = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < 4; ++c) {
+        const uint64_t m = __ballot(cls == c);
+        if (cls == c) rank_in_wave = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (lane == 0) class_count[wave][c] = (uint32_t)__popcll(m);
+    }
+    __syncthreads();
+    if (valid) {
+        uint32_t pos = rank_in_wave;
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c)
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w)
+                if (c < cls || (c == cls && w < wave)) pos += class_count[w][c];
+        order[pos] = (uint16_t)tid;
+    }
+    __syncthreads();
+
+    // round 2: the tid-th tile in class order
+    if (valid) {
+        const uint32_t t = order[tid];
+        const uint32_t inf = info[t];
+        const uint32_t meta16 = quantize_row<G, BF16>(lds + t * B::STRIDE, (inf & 0x80u) != 0, (inf & 0x100u) ? 4u : 3u,
+                                                      pay + (inf >> 9));
+        const uint64_t j = j0 + t;
         reinterpret_cast<uint16_t *>(packed + lay.scale)[j] = (uint16_t)meta16;
         reinterpret_cast<uint16_t *>(packed + lay.zero)[j] = (uint16_t)(meta16 >> 16);
-        packed[lay.pivot + j] = (uint8_t)pivot;
+        packed[lay.pivot + j] = (uint8_t)inf;
     }
     __syncthreads();
 
