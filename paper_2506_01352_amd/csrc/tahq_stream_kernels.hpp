@@ -377,20 +377,25 @@ __device__ __forceinline__ uint32_t analyse_row(uint8_t *row, float tau, float e
     return flag ? (0x80u | d) : 0u;
 }
 
-// The rest of the encoder for one tile whose row already carries P_d: Eq. 4 on outlier tiles, range,
-// quantizer parameters, codes, and the tile's LSB-first bit string written as b units at `dst` (LDS).
-// Returns scale | zero << 16.
+// The rest of the encoder for one tile, in two steps with a workgroup barrier between them (the payload
+// buffer that step 2 writes shares LDS with the rows that step 1 reads).
+// Step 1: the row (which already carries P_d) into registers; Eq. 4 on outlier tiles.
 template <int G, bool BF16>
-__device__ __forceinline__ uint32_t quantize_row(const uint8_t *row, bool flag, uint32_t b,
-                                                 typename Unit<G>::type *dst)
+__device__ __forceinline__ void transform_row(const uint8_t *row, bool flag, float *x)
 {
-    float x[G];
     read_tile<G, BF16>(row, x);
     if (flag) {
         butterfly<G>(x);
 #pragma unroll
         for (int k = 0; k < G; ++k) x[k] = x[k] * TileConst<G>::c;
     }
+}
+
+// Step 2: range, quantizer parameters, codes, and the tile's LSB-first bit string written as b units at
+// `dst` (LDS).  Returns scale | zero << 16.
+template <int G>
+__device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, typename Unit<G>::type *dst)
+{
     float mn = fmin3(x[0], x[1], x[2]), mx = fmax3(x[0], x[1], x[2]);
 #pragma unroll
     for (int k = 3; k + 1 < G; k += 2) { mn = fmin3(mn, x[k], x[k + 1]); mx = fmax3(mx, x[k], x[k + 1]); }
@@ -416,7 +421,7 @@ __device__ __forceinline__ uint32_t quantize_row(const uint8_t *row, bool flag, 
         float q[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            q[i] = __builtin_fminf(__builtin_fmaxf(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f), Lv);
+            q[i] = __builtin_amdgcn_fmed3f(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f, Lv);   // clamp; a NaN gives 0
         const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
         g4[g] = (uint32_t)acc;
     }
@@ -448,14 +453,20 @@ __device__ __forceinline__ uint32_t quantize_row(const uint8_t *row, bool flag, 
     return s16 | (z16 << 16);
 }
 
+// Occupancy hint: with small tiles the kernel fits four workgroups per compute unit if it stays within
+// 128 vector registers.
+template <int G, int ESIZE>
+struct QuantPackOccupancy { static constexpr int WAVES_PER_SIMD = (G * ESIZE <= 128) ? 4 : 1; };
+
 // One workgroup per batch of TILES tiles, in two rounds.  Round 1: lane i examines tile i (Eq. 3, pivot
 // swap in LDS).  The tiles are then regrouped by class -- (plain | transformed) x (3 | 4 bit) -- so that in
 // round 2, where lane p takes the p-th tile in class order, most wavefronts hold a single class: the
 // Hadamard butterfly runs only in the wavefronts that hold transformed tiles, and the 3-/4-bit packing
-// paths rarely both run.  (This kernel is bound by vector-ALU issue; its loads are covered by the
-// other resident workgroups.)
+// paths rarely both run.  The payload buffer reuses the rows' LDS once every lane holds its tile in
+// registers, which keeps the workgroup small enough for four to share a compute unit: this kernel
+// lives on the loads of its neighbours being in flight while it computes.
 template <int G, bool BF16>
-__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
+__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES), (QuantPackOccupancy<G, BF16 ? 2 : 4>::WAVES_PER_SIMD))
 void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Layout lay, uint32_t T, float tau,
                   float eps_ratio)
 {
@@ -463,11 +474,12 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     using B = Batch<G, ES>;
     using U = typename Unit<G>::type;
     constexpr int WAVES = (B::TILES + 63) / 64;
+    static_assert(sizeof(U) * 4 * B::TILES <= (size_t)B::LDS_BYTES, "payload buffer must fit in the rows");
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
-    __shared__ __attribute__((aligned(16))) U pay[B::TILES * 4];
     __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == 4) << 8 | rel << 9
     __shared__ uint16_t order[B::TILES];         // tiles in class order
     __shared__ uint32_t class_count[WAVES][4];
+    U *pay = reinterpret_cast<U *>(lds);         // valid only after every lane has left the rows
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
     const uint32_t left = (uint32_t)(T - j0);
@@ -513,11 +525,16 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     __syncthreads();
 
     // round 2: the tid-th tile in class order
+    float x[G];
+    uint32_t t = 0, inf = 0;
     if (valid) {
-        const uint32_t t = order[tid];
-        const uint32_t inf = info[t];
-        const uint32_t meta16 = quantize_row<G, BF16>(lds + t * B::STRIDE, (inf & 0x80u) != 0, (inf & 0x100u) ? 4u : 3u,
-                                                      pay + (inf >> 9));
+        t = order[tid];
+        inf = info[t];
+        transform_row<G, BF16>(lds + t * B::STRIDE, (inf & 0x80u) != 0, x);
+    }
+    __syncthreads();                             // the rows are dead: their LDS becomes the payload buffer
+    if (valid) {
+        const uint32_t meta16 = quantize_values<G>(x, (inf & 0x100u) ? 4u : 3u, pay + (inf >> 9));
         const uint64_t j = j0 + t;
         reinterpret_cast<uint16_t *>(packed + lay.scale)[j] = (uint16_t)meta16;
         reinterpret_cast<uint16_t *>(packed + lay.zero)[j] = (uint16_t)(meta16 >> 16);
