@@ -57,7 +57,7 @@ struct LaunchEntropy {
         static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_entropy<G, BF16>), B::TILES);
         const uint32_t unit_batches = hist0 ? (uint32_t)(n_per_unit / B::TILES) : 1u;
         hipLaunchKernelGGL((k_entropy<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, d_in, d_H, T,
-                           eps_l1, eps_log, hist0, unit_batches, 3u * kHistBins);
+                           eps_l1, eps_log, hist0, unit_batches, kDigit0Bins);
     }
     static bool can_fuse_histogram(uint64_t n_per_unit) { return n_per_unit % Batch<G, BF16 ? 2 : 4>::TILES == 0; }
 };
@@ -201,30 +201,30 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     const uint32_t zero_words = select ? (uint32_t)(ws.zero_bytes / 4) : 0u;
     if (phases & TAHQ_PHASE_PROLOGUE)
         hipLaunchKernelGGL(k_prologue, dim3(select ? 32 : 1), dim3(256), 0, st, packed, hdr, pads,
-                           reinterpret_cast<uint32_t *>(wsb + ws.hist), zero_words);
+                           reinterpret_cast<uint32_t *>(wsb + ws.hist0), zero_words);
 
     if (select) {
         float *H = reinterpret_cast<float *>(wsb + ws.keys);
-        uint32_t *hist = reinterpret_cast<uint32_t *>(wsb + ws.hist);
+        uint32_t *hist0 = reinterpret_cast<uint32_t *>(wsb + ws.hist0);
+        uint32_t *coarse = reinterpret_cast<uint32_t *>(wsb + ws.coarse);
+        uint32_t *partial = reinterpret_cast<uint32_t *>(wsb + ws.partial);
         uint32_t *state = reinterpret_cast<uint32_t *>(wsb + ws.state);
         uint32_t *seg = reinterpret_cast<uint32_t *>(wsb + ws.seg);
         uint8_t *sel = wsb + ws.sel;
         // the entropy kernel builds the first-digit histogram itself when units are whole batches
         bool fused = false;
         dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
-        if (phases & TAHQ_PHASE_ENTROPY) launch_entropy(s, cfg, d_in, H, hist, st);
+        if (phases & TAHQ_PHASE_ENTROPY) launch_entropy(s, cfg, d_in, H, hist0, st);
         if (phases & TAHQ_PHASE_SELECT) {
-            // few, fat blocks: every block flushes up to 2048 bins with global atomics
-            uint32_t hb = (uint32_t)((s.n + 16383) / 16384);
-            if (hb > 64) hb = 64;
             const uint32_t n32 = (uint32_t)s.n, k32 = (uint32_t)s.k;
+            const dim3 rgrid(ws.hb, s.U);
             if (!fused)
-                hipLaunchKernelGGL((k_radix_pass<0, 8>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
-            hipLaunchKernelGGL((k_radix_pass<1, 0>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
-            hipLaunchKernelGGL((k_radix_pass<2, 0>), dim3(hb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, hist, state);
+                hipLaunchKernelGGL((k_radix_pass<0, 8>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
+            hipLaunchKernelGGL((k_radix_pass<1, 0>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
+            hipLaunchKernelGGL((k_radix_pass<2, 0>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
             const uint32_t sb = (ws.nseg + 3) / 4;
             hipLaunchKernelGGL(k_seg_count, dim3(sb, s.U), dim3(256), 0, st, (const float *)H, n32, ws.nseg,
-                               (const uint32_t *)hist, state, seg);
+                               (const uint32_t *)coarse, (const uint32_t *)partial, ws.hb, state, seg);
             const int aligned = (s.n % 64 == 0) ? 1 : 0;
             hipLaunchKernelGGL(k_assign, dim3(sb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, ws.nseg,
                                (const uint32_t *)state, (const uint32_t *)seg, bitmap, ranks, sel, aligned);

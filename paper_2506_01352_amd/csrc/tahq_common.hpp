@@ -24,18 +24,23 @@ struct Layout {
 };
 
 constexpr uint32_t kSegTiles = 1024;     // tiles one wavefront handles in the selection kernels
-constexpr uint32_t kHistBins = 2048;
+constexpr uint32_t kHistBins = 2048;      // bins of radix digits 1 and 2 (11 bits each)
+constexpr uint32_t kDigit0Bins = 1024;    // bins of radix digit 0 (key bits 31..22)
+constexpr uint32_t kRadixKeysPerBlock = 8192;
 
 struct Workspace {
     // offsets in bytes from the workspace base
-    uint64_t hist;       // uint32[U][3][kHistBins]           (zeroed per call)
+    uint64_t hist0;      // uint32[U][kDigit0Bins]: first-digit histogram      (zeroed per call)
+    uint64_t coarse;     // uint32[U][2][64]: super-bin totals of digits 1, 2   (zeroed per call)
     uint64_t state;      // uint32[U][8] selection state
-    uint64_t zero_bytes; // bytes from `hist` that must be zero before the selection starts
+    uint64_t zero_bytes; // bytes from `hist0` that must be zero before the selection starts
+    uint64_t partial;    // uint32[U][2][hb][kHistBins]: per-workgroup histograms of digits 1, 2
     uint64_t keys;       // float[T] entropies
     uint64_t seg;        // uint32[U][nseg][2]: keys equal to / above the threshold, per segment
     uint64_t sel;        // uint8[T] (only when n % 64 != 0)
     uint64_t total;
     uint32_t nseg;       // segments per ranking unit
+    uint32_t hb;         // workgroups per ranking unit in the radix passes
 };
 
 inline uint64_t pad64(uint64_t x) { return (x + 63u) & ~uint64_t(63); }
@@ -80,11 +85,15 @@ void make_layout(const Shape &s, Layout *L)
 void make_workspace(const Shape &s, Workspace *w)
 {
     w->nseg = (uint32_t)((s.n + kSegTiles - 1) / kSegTiles);
+    uint64_t hb = (s.n + kRadixKeysPerBlock - 1) / kRadixKeysPerBlock;
+    w->hb = (uint32_t)(hb > 64 ? 64 : hb);
     uint64_t off = 0;
-    w->hist = off;  off += (uint64_t)s.U * 3 * kHistBins * 4;
-    w->state = off; off += (uint64_t)s.U * 8 * 4;
+    w->hist0 = off;  off += (uint64_t)s.U * kDigit0Bins * 4;
+    w->coarse = off; off += (uint64_t)s.U * 2 * 64 * 4;
+    w->state = off;  off += (uint64_t)s.U * 8 * 4;
     w->zero_bytes = off;
     off = pad256(off);
+    w->partial = off; off = pad256(off + (uint64_t)s.U * 2 * w->hb * kHistBins * 4);
     w->keys = off;  off = pad256(off + s.T * 4);
     w->seg = off;   off = pad256(off + (uint64_t)s.U * w->nseg * 8);
     w->sel = off;   off = pad256(off + s.T);

@@ -11,6 +11,11 @@
 // Kernels never wait on each other inside a launch: every dependency is a launch boundary, and the
 // small reductions a later kernel needs (which bin holds the k-th key, prefix over segments) are
 // recomputed by every block from a few KB of global data.
+//
+// Histograms of digits 1 and 2 are kept in two levels so that no address takes more than a handful of
+// global atomics: every workgroup stores its own 2048-bin histogram with plain stores and adds only the
+// totals of its 64 super-bins (32 bins each) atomically.  The reader picks the super-bin from the 64
+// totals, then sums the workgroups' counts for the 32 bins inside it.
 #pragma once
 #include "tahq_common.hpp"
 #include "tahq_stream_kernels.hpp"
@@ -63,6 +68,43 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
     *rem = (uint32_t)__shfl((int)found_rem, src, 64);
 }
 
+// Two-level variant of pick_bin for digits 1 and 2: `coarse` holds the 64 super-bin totals, `partial` the
+// `hb` per-workgroup histograms.  Run by one full wavefront; result in every lane.
+__device__ __forceinline__ void pick_bin_two_level(const uint32_t *__restrict__ coarse,
+                                                   const uint32_t *__restrict__ partial, uint32_t hb, uint32_t want,
+                                                   uint32_t *bin, uint32_t *rem)
+{
+    const int lane = threadIdx.x & 63;
+    // super-bins from the top: lane l looks at super-bin 63 - l
+    const uint32_t c = coarse[63 - lane];
+    const uint32_t above = wave_incl_scan(c) - c;
+    const bool hit = above < want && want <= above + c;
+    const uint64_t who = __ballot(hit);
+    const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
+    const uint32_t sb = 63u - (uint32_t)src;
+    const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
+    // the 32 bins of that super-bin, from the top: lanes l and l+32 split the workgroups of bin 31 - (l & 31)
+    const uint32_t b_in = 31u - ((uint32_t)lane & 31u);
+    // (all loads first, then the sum: a rolled loop would pay one memory latency per workgroup)
+    uint32_t part[32];
+#pragma unroll
+    for (uint32_t i = 0; i < 32; ++i) {
+        const uint32_t blk = ((uint32_t)lane >> 5) + 2 * i;
+        part[i] = blk < hb ? partial[(uint64_t)blk * kHistBins + sb * 32 + b_in] : 0u;
+    }
+    uint32_t sum = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 32; ++i) sum += part[i];
+    sum += (uint32_t)__shfl_xor((int)sum, 32, 64);
+    const uint32_t mine = lane < 32 ? sum : 0u;
+    const uint32_t above2 = wave_incl_scan(mine) - mine;
+    const bool hit2 = lane < 32 && above2 < want2 && want2 <= above2 + mine;
+    const uint64_t who2 = __ballot(hit2);
+    const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
+    *bin = sb * 32 + (31u - (uint32_t)src2);
+    *rem = want2 - (uint32_t)__shfl((int)above2, src2, 64);
+}
+
 // One radix pass.  Digits: pass 0 = key bits 31..22 (1024 bins), pass 1 = bits 21..11, pass 2 = bits 10..0
 // (2048 bins each).  Pass p > 0 first derives, from the histogram of pass p-1, the bin chosen there (every
 // block does this; block 0 of the unit also records it in `state`), then histograms digit p of the keys
@@ -71,26 +113,27 @@ __device__ __forceinline__ void pick_bin(const uint32_t *__restrict__ hist, uint
 // (it sees only a handful of distinct digits, which would serialize the LDS atomics).
 template <int PASS, int PEEL>
 __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H, uint32_t n, uint32_t k,
-                                                    uint32_t *__restrict__ hist, uint32_t *__restrict__ state)
+                                                    uint32_t *__restrict__ hist0, uint32_t *__restrict__ coarse,
+                                                    uint32_t *__restrict__ partial, uint32_t *__restrict__ state)
 {
-    constexpr int BINS = PASS == 0 ? kDigit0Bins : (int)kHistBins;
+    constexpr int BINS = PASS == 0 ? (int)kDigit0Bins : (int)kHistBins;
     __shared__ uint32_t lh[BINS];
     __shared__ uint32_t chosen[2];
-    const uint32_t u = blockIdx.y;
+    const uint32_t u = blockIdx.y, hb = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63;
-    uint32_t *uh = hist + ((uint64_t)u * 3 + PASS) * kHistBins;
     uint32_t *ust = state + (uint64_t)u * 8;
     const float *uH = H + (uint64_t)u * n;
+    uint32_t *ucoarse = coarse + (uint64_t)u * 2 * 64;                    // [2][64]
+    uint32_t *upartial = partial + (uint64_t)u * 2 * hb * kHistBins;      // [2][hb][2048]
 
     for (int i = tid; i < BINS; i += 256) lh[i] = 0;
 
     uint32_t want_hi = 0;
     if (PASS > 0) {
         if (tid < 64) {
-            const uint32_t want = PASS == 1 ? k : ust[ST_KREM0];
             uint32_t bin, rem;
-            if (PASS == 1) pick_bin<kDigit0Bins>(uh - kHistBins, want, &bin, &rem);
-            else pick_bin<kHistBins>(uh - kHistBins, want, &bin, &rem);
+            if (PASS == 1) pick_bin<kDigit0Bins>(hist0 + (uint64_t)u * kDigit0Bins, k, &bin, &rem);
+            else pick_bin_two_level(ucoarse, upartial, hb, ust[ST_KREM0], &bin, &rem);
             if (lane == 0) {
                 chosen[0] = bin;
                 chosen[1] = rem;
@@ -138,15 +181,28 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
         }
     }
     __syncthreads();
-    for (int i = tid; i < BINS; i += 256)
-        if (lh[i]) atomicAdd(&uh[i], lh[i]);
+    if (PASS == 0) {
+        for (int i = tid; i < BINS; i += 256)
+            if (lh[i]) atomicAdd(&hist0[(uint64_t)u * kDigit0Bins + i], lh[i]);
+    } else {
+        // my histogram with plain stores; only the 64 super-bin totals go through atomics
+        uint32_t *mine = upartial + ((uint64_t)(PASS - 1) * hb + blockIdx.x) * kHistBins;
+        for (int i = tid; i < BINS; i += 256) mine[i] = lh[i];
+        if (tid < 64) {
+            uint32_t tot = 0;
+#pragma unroll 8
+            for (int i = 0; i < 32; ++i) tot += lh[32 * tid + ((i + tid) & 31)];     // rotated: no bank conflicts
+            if (tot) atomicAdd(&ucoarse[(PASS - 1) * 64 + tid], tot);
+        }
+    }
 }
 
 // Per segment of kSegTiles tiles (one wavefront each): how many keys equal K* and how many exceed it.
 // K* and `take` come from the pass-2 histogram; every block derives them, block 0 records them.
 __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, uint32_t n, uint32_t nseg,
-                                                   const uint32_t *__restrict__ hist, uint32_t *__restrict__ state,
-                                                   uint32_t *__restrict__ seg)
+                                                   const uint32_t *__restrict__ coarse,
+                                                   const uint32_t *__restrict__ partial, uint32_t hb,
+                                                   uint32_t *__restrict__ state, uint32_t *__restrict__ seg)
 {
     __shared__ uint32_t chosen[2];
     const uint32_t u = blockIdx.y;
@@ -154,7 +210,8 @@ __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, 
     uint32_t *ust = state + (uint64_t)u * 8;
     if (tid < 64) {
         uint32_t bin, rem;
-        pick_bin<kHistBins>(hist + ((uint64_t)u * 3 + 2) * kHistBins, ust[ST_KREM1], &bin, &rem);
+        pick_bin_two_level(coarse + ((uint64_t)u * 2 + 1) * 64, partial + ((uint64_t)u * 2 + 1) * hb * kHistBins, hb,
+                           ust[ST_KREM1], &bin, &rem);
         const uint32_t key = (ust[ST_BIN0] << 22) | (ust[ST_BIN1] << 11) | bin;
         if (lane == 0) {
             chosen[0] = key;
@@ -209,33 +266,44 @@ __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uin
     const uint32_t s0 = blockIdx.x * 4;
 
     if (tid < 64) {
-        // lane l owns the run of segments [l*run, (l+1)*run) of the s0 segments before this block
-        const uint32_t run = (s0 + 63) / 64;
-        const uint32_t lo = (uint32_t)lane * run;
-        const uint32_t hi = lo + run < s0 ? lo + run : s0;
-        uint32_t eq_sum = 0;
-        for (uint32_t i = lo; i < hi; ++i) eq_sum += useg[2 * i];
-        uint32_t eq_before = wave_incl_scan(eq_sum) - eq_sum;
-        uint32_t sel_sum = 0;
-        for (uint32_t i = lo; i < hi; ++i) {
-            const uint32_t eq = useg[2 * i], gt = useg[2 * i + 1];
-            const uint32_t left = eq_before < take ? take - eq_before : 0u;
-            sel_sum += gt + (eq < left ? eq : left);
-            eq_before += eq;
+        // Sums over the s0 segments before this block, 512 segments per sweep: lane l owns the 8 consecutive
+        // segments 8l .. 8l+7 of the sweep (loaded at once), a wave scan orders the lanes, `eq_run` / `rank_run`
+        // carry the totals from sweep to sweep.
+        const uint2 *pairs = reinterpret_cast<const uint2 *>(useg);
+        uint32_t eq_run = 0, rank_run = u * k;
+        for (uint32_t base = 0; base < s0; base += 512) {
+            uint2 e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t sidx = base + (uint32_t)lane * 8 + i;
+                e[i] = sidx < s0 ? pairs[sidx] : make_uint2(0u, 0u);
+            }
+            uint32_t eq_sum = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) eq_sum += e[i].x;
+            const uint32_t eq_incl = wave_incl_scan(eq_sum);
+            uint32_t eq_before = eq_run + eq_incl - eq_sum;
+            uint32_t sel_sum = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t left = eq_before < take ? take - eq_before : 0u;
+                sel_sum += e[i].y + (e[i].x < left ? e[i].x : left);
+                eq_before += e[i].x;
+            }
+            const uint32_t sel_incl = wave_incl_scan(sel_sum);
+            eq_run += (uint32_t)__shfl((int)eq_incl, 63, 64);
+            rank_run += (uint32_t)__shfl((int)sel_incl, 63, 64);
         }
-        const uint32_t sel_incl = wave_incl_scan(sel_sum);
-        // totals over all preceding segments sit in lane 63
-        uint32_t eq_run = (uint32_t)__shfl((int)eq_before, 63, 64);
-        uint32_t rank_run = u * k + (uint32_t)__shfl((int)sel_incl, 63, 64);
         // the block's own four segments, in order
+        uint2 own[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) own[w] = s0 + w < nseg ? pairs[s0 + w] : make_uint2(0u, 0u);
+#pragma unroll
         for (int w = 0; w < 4; ++w) {
             if (lane == 0) { base_eq[w] = eq_run; base_rank[w] = rank_run; }
-            if (s0 + w < nseg) {
-                const uint32_t eq = useg[2 * (s0 + w)], gt = useg[2 * (s0 + w) + 1];
-                const uint32_t left = eq_run < take ? take - eq_run : 0u;
-                rank_run += gt + (eq < left ? eq : left);
-                eq_run += eq;
-            }
+            const uint32_t left = eq_run < take ? take - eq_run : 0u;
+            rank_run += own[w].y + (own[w].x < left ? own[w].x : left);
+            eq_run += own[w].x;
         }
     }
     __syncthreads();

@@ -152,7 +152,7 @@ __device__ __forceinline__ uint32_t order_key(float h)
 }
 
 constexpr int kDigit0Bits = 10;                  // first radix digit of the selection: key bits 31..22
-constexpr int kDigit0Bins = 1 << kDigit0Bits;
+static_assert((1u << kDigit0Bits) == kDigit0Bins, "digit 0 width");
 
 // Persistent workgroups: workgroup w handles a contiguous run of full batches.  The next batch's loads
 // are issued before the current batch is processed, and a batch's result is stored one iteration later,
@@ -180,11 +180,11 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
     const uint32_t last = first + per < nfull ? first + per : nfull;      // my batches: [first, last)
 
     if (hist0) {
-        for (int i = tid; i < kDigit0Bins; i += B::TILES) lh[i] = 0;
+        for (int i = tid; i < (int)kDigit0Bins; i += B::TILES) lh[i] = 0;
     }
     auto flush = [&](uint32_t unit) {
         __syncthreads();
-        for (int i = tid; i < kDigit0Bins; i += B::TILES) {
+        for (int i = tid; i < (int)kDigit0Bins; i += B::TILES) {
             const uint32_t c = lh[i];
             if (c) { atomicAdd(&hist0[(uint64_t)unit * hist_stride + i], c); lh[i] = 0; }
         }
