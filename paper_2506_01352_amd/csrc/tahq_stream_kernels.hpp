@@ -25,7 +25,21 @@ struct Batch {
 // next batch can be in flight while the current one is being processed.  Thread t moves the 16-byte
 // chunks t, t + TILES, t + 2 TILES, ... of the batch (coalesced).  FULL: all TILES tiles exist, no
 // per-thread conditions (so that the compiler can count outstanding memory operations exactly).
-template <int G, int ESIZE, bool FULL>
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte global load; STREAM marks data that will not be read again soon (non-temporal hint).
+template <bool STREAM>
+__device__ __forceinline__ uint4 load16(const uint8_t *p)
+{
+    if constexpr (STREAM) {
+        const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        return make_uint4(t.x, t.y, t.z, t.w);
+    } else {
+        return *reinterpret_cast<const uint4 *>(p);
+    }
+}
+
+template <int G, int ESIZE, bool FULL, bool STREAM = false>
 __device__ __forceinline__ void load_batch(const void *__restrict__ in, uint64_t j0, uint32_t nvalid,
                                            uint4 (&v)[Batch<G, ESIZE>::CHUNKS])
 {
@@ -36,10 +50,10 @@ __device__ __forceinline__ void load_batch(const void *__restrict__ in, uint64_t
     for (int i = 0; i < B::CHUNKS; ++i) {
         const uint32_t q = (uint32_t)i * B::TILES + tid;
         if constexpr (FULL) {
-            v[i] = *reinterpret_cast<const uint4 *>(src + (uint64_t)q * 16);
+            v[i] = load16<STREAM>(src + (uint64_t)q * 16);
         } else {
             v[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (q / B::CHUNKS < nvalid) v[i] = *reinterpret_cast<const uint4 *>(src + (uint64_t)q * 16);
+            if (q / B::CHUNKS < nvalid) v[i] = load16<STREAM>(src + (uint64_t)q * 16);
         }
     }
 }
@@ -68,8 +82,12 @@ __device__ __forceinline__ void stage_out(void *__restrict__ out, uint64_t j0, u
     for (int i = 0; i < B::CHUNKS; ++i) {
         const uint32_t q = (uint32_t)i * B::TILES + tid;
         const uint32_t tile = q / B::CHUNKS, sub = q % B::CHUNKS;
-        if (FULL || tile < nvalid)
-            *reinterpret_cast<uint4 *>(dst + (uint64_t)q * 16) = *reinterpret_cast<const uint4 *>(lds + tile * B::STRIDE + sub * 16);
+        if (FULL || tile < nvalid) {
+            // streaming store: the decoded tensor is not read again by this library
+            const uint4 val = *reinterpret_cast<const uint4 *>(lds + tile * B::STRIDE + sub * 16);
+            const u32x4 vv = {val.x, val.y, val.z, val.w};
+            __builtin_nontemporal_store(vv, reinterpret_cast<u32x4 *>(dst + (uint64_t)q * 16));
+        }
     }
 }
 
@@ -487,8 +505,8 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     const bool full = nvalid == (uint32_t)B::TILES;
 
     uint4 v[B::CHUNKS];
-    if (full) load_batch<G, ES, true>(in, j0, nvalid, v);
-    else load_batch<G, ES, false>(in, j0, nvalid, v);
+    if (full) load_batch<G, ES, true, true>(in, j0, nvalid, v);      // second and last read of the tensor
+    else load_batch<G, ES, false, true>(in, j0, nvalid, v);
     BatchMeta<B::TILES> meta;
     load_meta<B::TILES>(packed, lay, j0, T, 0u, meta);
     if (full) store_batch<G, ES, true>(v, nvalid, lds);
