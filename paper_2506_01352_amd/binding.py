@@ -3,7 +3,8 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libtahq.so")
+# TAHQ_LIBRARY lets an experiment load another build of the same library
+_LIB_PATH = os.environ.get("TAHQ_LIBRARY") or os.path.join(HERE, "libtahq.so")
 
 F32, BF16 = 0, 1
 

@@ -210,7 +210,12 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
     };
 
     uint4 v[B::CHUNKS];
-    if (first < last) load_batch<G, ES, true>(in, (uint64_t)first * B::TILES, B::TILES, v);
+    // non-temporal loads: the tensor is much larger than any cache, and keeping part of it for the second
+    // pass measured slower than streaming all of it
+    auto load_full = [&](uint32_t batch) {
+        load_batch<G, ES, true, true>(in, (uint64_t)batch * B::TILES, B::TILES, v);
+    };
+    if (first < last) load_full(first);
     float h_prev = 0.0f;
     uint64_t j_prev = 0;
     bool have_prev = false;
@@ -223,7 +228,7 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
         store_batch<G, ES, true>(v, B::TILES, lds);
         __syncthreads();
         if (have_prev) H[j_prev] = h_prev;
-        if (batch + 1 < last) load_batch<G, ES, true>(in, (uint64_t)(batch + 1) * B::TILES, B::TILES, v);
+        if (batch + 1 < last) load_full(batch + 1);
         h_prev = entropy_of_row<G, BF16>(row, eps_l1, eps_log);
         if (hist0) atomicAdd(&lh[order_key(h_prev) >> (32 - kDigit0Bits)], 1u);
         j_prev = (uint64_t)batch * B::TILES + tid;
