@@ -80,12 +80,13 @@ struct LaunchQuantPack {
 
 template <int G, bool BF16>
 struct LaunchDecode {
-    static void run(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, hipStream_t st)
+    static void run(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total4, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
         static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_decode<G, BF16>), B::TILES);
-        hipLaunchKernelGGL((k_decode<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, packed, d_out, lay, T);
+        hipLaunchKernelGGL((k_decode<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, packed, d_out, lay, T,
+                           total4);
     }
 };
 
@@ -266,7 +267,7 @@ tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t pac
     if (packed_bytes < lay.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
     if (misaligned(d_packed) || misaligned(d_out)) return TAHQ_ERR_MISALIGNED;
     dispatch<LaunchDecode>(s.G, out_dtype == TAHQ_BF16, static_cast<const uint8_t *>(d_packed), d_out, lay,
-                           (uint32_t)s.T, (hipStream_t)stream);
+                           (uint32_t)s.T, (uint32_t)(s.U * s.k), (hipStream_t)stream);
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
 

@@ -665,16 +665,16 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
     }
 }
 
-// Persistent workgroups over the full batches, software-pipelined: while batch i is decoded, the payload
-// span, bit map words and per-tile metadata of batch i+1 are in flight; the stores of batch i are issued
-// at the end of its iteration and drain during the next one.  The fast loop has no per-thread conditions
-// on global memory operations, so every wait counts exactly the operations it must leave outstanding.
-// The only two-step dependency -- the rank-table entry that locates a batch's payload -- is taken out of
-// the loop: the entries of all batches of this workgroup are read into LDS up front.
+// Persistent workgroups over contiguous runs of full batches, software-pipelined: while batch i is decoded,
+// the payload span, bit map words and per-tile metadata of batch i+1 are in flight; the rows of batch i are
+// written out one iteration late, just before the next loads are issued, so that no wait for loads has a
+// younger store in front of it.  The fast loop has no per-thread conditions on global memory operations.
+// The only two-step dependency -- the rank-table entries that locate a batch's payload and give its length
+// -- is taken out of the loop: the entries of the workgroup's batches are read into LDS up front.
 // The ragged last batch is handled after the loop by one workgroup.
 template <int G, bool OUT_BF16>
 __global__ __launch_bounds__((Batch<G, OUT_BF16 ? 2 : 4>::TILES))
-void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout lay, uint32_t T)
+void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout lay, uint32_t T, uint32_t total_four_bit)
 {
     constexpr int ES = OUT_BF16 ? 2 : 4;
     using B = Batch<G, ES>;
@@ -682,42 +682,49 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     using Meta = BatchMeta<B::TILES>;
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
     __shared__ __attribute__((aligned(16))) U pay[B::TILES * 4];
-    __shared__ uint32_t rank_lds[B::TILES];
+    __shared__ uint32_t rank_lds[B::TILES + 1];
     const int tid = threadIdx.x;
     const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
+    const uint32_t per = (nfull + gridDim.x - 1) / gridDim.x;
+    const uint32_t first = blockIdx.x * per;
+    const uint32_t last = first + per < nfull ? first + per : nfull;      // my batches: [first, last)
     const uint16_t *scale = reinterpret_cast<const uint16_t *>(packed + lay.scale);
     const uint16_t *zero = reinterpret_cast<const uint16_t *>(packed + lay.zero);
     const uint8_t *pivot = packed + lay.pivot;
     const uint32_t *ranks = reinterpret_cast<const uint32_t *>(packed + lay.ranks);
     const U *payload = reinterpret_cast<const U *>(packed + lay.payload);
-    const uint64_t last_unit = (lay.total - lay.payload) / sizeof(U) - 1;    // last unit of the stream
     uint8_t *row = lds + tid * B::STRIDE;
     uint32_t lane_zero = 0;
     asm volatile("" : "+v"(lane_zero));
     const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap) + lane_zero;
 
-    // rank-table entries of TILES consecutive batches of this workgroup, starting at its iteration `first`
-    auto load_rank_window = [&](uint32_t first) {
-        const uint64_t bb = (uint64_t)blockIdx.x + ((uint64_t)first + tid) * gridDim.x;
-        if (bb < nfull) rank_lds[tid] = ranks[bb * (B::TILES / 64)];
+    // 4-bit tiles before batch b (for the batch past the end of the tensor: all of them)
+    auto rank_of_batch = [&](uint64_t b) {
+        return b * B::TILES < T ? ranks[b * (B::TILES / 64)] : total_four_bit;
+    };
+    // slots 0..TILES of the window hold the entries of batches wfirst .. wfirst + TILES
+    auto load_rank_window = [&](uint32_t wfirst) {
+        rank_lds[tid] = rank_of_batch((uint64_t)wfirst + tid);
+        if (tid == 0) rank_lds[B::TILES] = rank_of_batch((uint64_t)wfirst + B::TILES);
         __syncthreads();
     };
-    load_rank_window(0);
-    uint32_t wbase = 0;
+    uint32_t wfirst = first;
+    if (first < last) load_rank_window(wfirst);
 
     Meta m;            // bit map words of the batch whose loads are in flight / have just arrived
     U pre[4];
     uint32_t s16 = 0, z16 = 0, pv = 0;
-    // issue the loads of full batch `batch`, whose rank-table entry is slot `slot` of the LDS window
-    auto fetch = [&](uint32_t batch, uint32_t slot) {
+    // issue the loads of full batch `batch` (inside the current window)
+    auto fetch = [&](uint32_t batch) {
         const uint64_t j0 = (uint64_t)batch * B::TILES;
-        m.rank0 = rank_lds[slot];
+        m.rank0 = rank_lds[batch - wfirst];
+        const uint32_t total4 = rank_lds[batch - wfirst + 1] - m.rank0;
         const uint64_t base = 3ull * j0 + m.rank0;
 #pragma unroll
         for (int i = 0; i < 3; ++i) pre[i] = payload[base + (uint32_t)i * B::TILES + tid];
-        // the fourth unit may lie beyond the batch's span (it is then not used): keep it inside the stream
-        const uint64_t q3 = base + 3u * (uint32_t)B::TILES + (uint32_t)tid;
-        pre[3] = payload[q3 < last_unit ? q3 : last_unit];
+        // a thread's fourth unit exists only if the batch has more than `tid` four-bit tiles; otherwise the
+        // load is pointed at the batch's first unit (a line that is being read anyway) and ignored
+        pre[3] = payload[base + ((uint32_t)tid < total4 ? 3u * (uint32_t)B::TILES + (uint32_t)tid : 0u)];
 #pragma unroll
         for (int w = 0; w < Meta::WORDS; ++w) m.word[w] = bitmap[(j0 >> 6) + w];
         s16 = scale[j0 + tid];
@@ -725,31 +732,35 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         pv = pivot[j0 + tid];
     };
 
-    uint32_t batch = blockIdx.x, it = 0;
-    if (batch < nfull) fetch(batch, 0);
-    for (; batch < nfull; batch += gridDim.x, ++it) {
+    if (first < last) fetch(first);
+    bool have_prev = false;
+    uint32_t prev_batch = 0;
+    for (uint32_t batch = first; batch < last; ++batch) {
         uint32_t b, rel, total4;
         tile_pos<B::TILES>(m, tid, &b, &rel, &total4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) pay[(uint32_t)i * B::TILES + tid] = pre[i];
         const uint32_t my_s16 = s16, my_z16 = z16, my_pv = pv;
         __syncthreads();
+        if (have_prev) stage_out<G, ES, true>(out, (uint64_t)prev_batch * B::TILES, B::TILES, lds);
+        __syncthreads();
 
-        const uint32_t next = batch + gridDim.x;
-        if (next < nfull) {
-            if (it + 1 - wbase == (uint32_t)B::TILES) {      // once every TILES iterations
+        if (batch + 1 < last) {
+            if (batch + 1 - wfirst == (uint32_t)B::TILES) {      // once every TILES iterations
                 __syncthreads();
-                wbase = it + 1;
-                load_rank_window(wbase);
+                wfirst = batch + 1;
+                load_rank_window(wfirst);
             }
-            fetch(next, it + 1 - wbase);
+            fetch(batch + 1);
         }
         decode_row<G, OUT_BF16>(pay + rel, b, my_s16, my_z16, my_pv, row);
+        prev_batch = batch;
+        have_prev = true;
         __syncthreads();
-        stage_out<G, ES, true>(out, (uint64_t)batch * B::TILES, B::TILES, lds);
     }
+    if (have_prev) stage_out<G, ES, true>(out, (uint64_t)prev_batch * B::TILES, B::TILES, lds);
 
-    if (tail != 0 && blockIdx.x == nfull % gridDim.x) {
+    if (tail != 0 && blockIdx.x == gridDim.x - 1) {
         __syncthreads();
         const uint64_t j0 = (uint64_t)nfull * B::TILES;
         load_meta<B::TILES>(packed, lay, j0, T, 0u, m);
