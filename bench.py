@@ -141,11 +141,23 @@ def main():
             tahq.tahq_decode(cfg, codec.packed, codec.out, codec.out_dtype, stream)
             e1.record(stream)
 
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # every EVENT_EVERY-th step of the timed region carries the two events (each costs a few microseconds of
+    # idle GPU); the other steps are plain tahq_encode + tahq_decode
+    EVENT_EVERY = 4
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range((args.steps + EVENT_EVERY - 1) // EVENT_EVERY)]
+
+    def plain_step():
+        tahq.tahq_encode(cfg, d_in, codec.packed, codec.workspace, stream)
+        tahq.tahq_decode(cfg, codec.packed, codec.out, codec.out_dtype, stream)
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for e0, e1 in evs:
-        step(e0, e1)
+    for i in range(args.steps):
+        if i % EVENT_EVERY == 0:
+            step(*evs[i // EVENT_EVERY])
+        else:
+            plain_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -158,7 +170,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-        "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": dom_ms,
+        "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": dom_ms, "launches_timed": len(evs),
     }
 
     out = {

@@ -263,3 +263,39 @@ def test_full_size_configs_bit_exact(tahq, index):
     got = got.numpy() if w.dtype == tahq.F32 else got.view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(got.view(np.uint32 if w.dtype == tahq.F32 else np.uint16),
                           want_out.view(np.uint32 if w.dtype == tahq.F32 else np.uint16))
+
+
+# ------------------------------------- every (tile width, dtype) pair, several batches and a ragged tail
+
+@pytest.mark.parametrize("G", (32, 64, 128))
+@pytest.mark.parametrize("dtype_name", ("f32", "bf16"))
+def test_all_tile_widths_and_dtypes_over_several_batches(tahq, G, dtype_name):
+    # a workgroup handles min(256, 32768 / tile bytes) tiles: take 3 full batches plus a ragged tail, with
+    # sample boundaries that fall inside batches
+    dtype = tahq.F32 if dtype_name == "f32" else tahq.BF16
+    tile_bytes = G * (4 if dtype == tahq.F32 else 2)
+    tiles_per_batch = min(256, 32768 // tile_bytes)
+    M = 3
+    S = (3 * tiles_per_batch + 37) // M
+    B = 2
+    rng = np.random.default_rng(G + (7 if dtype == tahq.F32 else 11))
+    x = rng.standard_normal((B, S, M * G)).astype(np.float32)
+    x[:, :, 5] *= 30.0
+    x[:, ::7, :] = rng.uniform(-8, 8, size=x[:, ::7, :].shape).astype(np.float32)
+    x[1, 3:9, :] = 0.0
+    xin = x if dtype == tahq.F32 else workloads.f32_to_bf16_bits(x)
+    for budget in (3.3, 4.0):
+        _say(f"[case] G={G} {dtype_name} shape={B}x{S}x{M * G} budget={budget}")
+        check_case(tahq, xin, B, S, M * G, G, dtype, budget)
+        check_case(tahq, xin, B, S, M * G, G, dtype, budget,
+                   out_dtype=(tahq.BF16 if dtype == tahq.F32 else tahq.F32))
+
+
+def test_many_ranking_units_with_few_tiles_each(tahq):
+    # 300 samples of 6 tiles: units smaller than a wavefront, a batch spans many units
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((300, 2, 192)).astype(np.float32)
+    x[:, :, 17] *= 12.0
+    _say("[case] 300 units x 6 tiles")
+    for budget in (3.34, 3.5, 3.67):
+        check_case(tahq, x, 300, 2, 192, 64, tahq.F32, budget)
