@@ -299,3 +299,42 @@ def test_many_ranking_units_with_few_tiles_each(tahq):
     _say("[case] 300 units x 6 tiles")
     for budget in (3.34, 3.5, 3.67):
         check_case(tahq, x, 300, 2, 192, 64, tahq.F32, budget)
+
+
+def test_nan_inf_and_huge_inputs_are_lossy_but_never_a_fault(tahq):
+    # Outside the contract: the result for the poisoned sample is unspecified, but nothing may fault or hang,
+    # and a clean sample in the same tensor must still match the oracle bit for bit (ranking is per sample).
+    rng = np.random.default_rng(9)
+    G, S, M = 64, 40, 8
+    x = rng.standard_normal((2, S, M * G)).astype(np.float32)
+    x[:, :, 11] *= 25.0
+    clean = x[1:2].copy()
+    x[0, 0, 3] = np.nan
+    x[0, 1, 70] = np.inf
+    x[0, 2, 130] = -np.inf
+    x[0, 3, :64] = 3e38
+    x[0, 4, 64:128] = np.nan
+    x[0, 5, 200] = 1e30
+    for dtype, conv in ((tahq.F32, lambda a: a), (tahq.BF16, workloads.f32_to_bf16_bits)):
+        _say(f"[case] non-finite inputs dtype={dtype}")
+        with np.errstate(all="ignore"):
+            xin = np.ascontiguousarray(conv(x))
+        cfg = tahq.make_config(2, S, M * G, G, dtype, 3.5)
+        H, packed, out = run_gpu(tahq, cfg, xin, tahq.F32)
+        # the clean sample alone, through the oracle
+        ocfg1 = o32.make_cfg(1, S, M * G, G, dtype, 3.5)
+        want = o32.encode(ocfg1, np.ascontiguousarray(conv(clean)))
+        n, k = S * M, o32.k_per_unit(ocfg1)
+        T = 2 * n
+        off2 = o64.section_offsets(T, G, 2, k)
+        off1 = o64.section_offsets(n, G, 1, k)
+        # per-tile sections of sample 1 sit at tile offset n
+        assert np.array_equal(packed[off2["pivot"] + n: off2["pivot"] + 2 * n], want[off1["pivot"]: off1["pivot"] + n])
+        assert np.array_equal(packed[off2["scale"] + 2 * n: off2["scale"] + 4 * n], want[off1["scale"]: off1["scale"] + 2 * n])
+        assert np.array_equal(packed[off2["zero"] + 2 * n: off2["zero"] + 4 * n], want[off1["zero"]: off1["zero"] + 2 * n])
+        assert np.array_equal(packed[off2["bitmap"] + n // 8: off2["bitmap"] + 2 * n // 8],
+                              want[off1["bitmap"]: off1["bitmap"] + n // 8])
+        pay1 = (G // 8) * (3 * n + k)
+        assert np.array_equal(packed[off2["payload"] + pay1: off2["total"]], want[off1["payload"]: off1["total"]])
+        want_out = o32.decode(ocfg1, want, o32.F32)
+        assert np.array_equal(out[n * G:].view(np.uint32), want_out.view(np.uint32))
