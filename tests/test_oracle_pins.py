@@ -221,6 +221,7 @@ def test_fp16_conversions_against_numpy_float16():
         assert o32.fp16_widen(int(h)) == float(np.uint16(h).view(np.float16))
 
 
+@pytest.mark.filterwarnings("ignore:overflow encountered")
 def test_fp16_directed_rounding_brackets_the_value():
     rng = np.random.default_rng(3)
     xs = rng.standard_normal(3000).astype(np.float32) * np.float32(10.0) ** rng.integers(-10, 5, 3000).astype(np.float32)
@@ -579,3 +580,27 @@ def test_workload_generators_are_seeded_and_prefix_stable():
     w2, big = workloads.generate(2, batch=2, seq=16)
     _, small = workloads.generate(2, batch=1, seq=16)
     assert np.array_equal(big[0], small[0])
+
+
+def test_outlier_threshold_is_strict():
+    # Eq. 3: "exceeds" -- a ratio of exactly tau does not trigger the transform
+    v = np.zeros(32, np.float32); v[7] = 2.0; v[3] = -1.0
+    assert o32.outlier(v, tau=2.0, eps_ratio=0.0) == (False, 7)
+    v[7] = np.nextafter(np.float32(2.0), np.float32(3.0))
+    assert o32.outlier(v, tau=2.0, eps_ratio=0.0) == (True, 7)
+
+
+def test_k_gives_the_mean_width_closest_to_the_budget():
+    # top-p% with p = budget - 3: among all integer tile counts, k makes 3 + k/n closest to the budget
+    rng = np.random.default_rng(15)
+    for _ in range(200):
+        n_tok = int(rng.integers(1, 40))
+        n = n_tok * 3
+        budget = float(np.float32(rng.uniform(3.0, 4.0)))
+        cfg = o32.make_cfg(1, n_tok, 96, 32, o32.F32, budget)
+        k = o32.k_per_unit(cfg)
+        gaps = np.abs(3.0 + np.arange(n + 1) / n - budget)
+        best = np.nonzero(np.isclose(gaps, gaps.min(), rtol=0, atol=1e-12))[0]
+        assert k in best, (n, budget, k, best)
+    cfg = o32.make_cfg(1, 4, 96, 32, o32.F32, 3.4)      # n = 12: 0.4 * 12 = 4.8 -> 5 tiles
+    assert o32.k_per_unit(cfg) == 5
