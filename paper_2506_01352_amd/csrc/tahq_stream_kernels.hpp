@@ -438,15 +438,29 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
     // codes, four at a time: q0 + m q1 + m^2 q2 + m^3 q3 is an exact integer below 2^16 in fp32
     const float m1 = (b == 4u) ? 16.0f : 8.0f;
     const float m2 = m1 * m1, m3 = m2 * m1;
+    // Every element lies in [mn, mx]; if z <= mn, (x - z) * rcp lies in [0, (mx - z) * rcp], and when that
+    // bound rounds to at most L the clamp is the identity and is skipped.  Both conditions can fail only when
+    // the binary16 metadata saturated (magnitudes beyond the contract).
     uint32_t g4[G / 4];
+    if (mnf <= mn && (mx - mnf) * rcp <= Lv + 0.25f) {
 #pragma unroll
-    for (int g = 0; g < G / 4; ++g) {
-        float q[4];
+        for (int g = 0; g < G / 4; ++g) {
+            float q[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            q[i] = __builtin_amdgcn_fmed3f(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f, Lv);   // clamp; a NaN gives 0
-        const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
-        g4[g] = (uint32_t)acc;
+            for (int i = 0; i < 4; ++i) q[i] = __builtin_rintf((x[4 * g + i] - mnf) * rcp);
+            const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
+            g4[g] = (uint32_t)acc;
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < G / 4; ++g) {
+            float q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                q[i] = __builtin_amdgcn_fmed3f(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f, Lv);
+            const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
+            g4[g] = (uint32_t)acc;
+        }
     }
     // LSB-first bit string of the tile as dwords
     uint32_t dw[G / 8];
