@@ -697,7 +697,11 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
     __shared__ __attribute__((aligned(16))) U pay[B::TILES * 4];
     __shared__ uint32_t rank_lds[B::TILES + 1];
-    const int tid = threadIdx.x;
+    constexpr int WAVES = (B::TILES + 63) / 64;
+    __shared__ uint2 tile_meta[B::TILES];        // per tile: scale | zero << 16, pivot byte | (b == 4) << 8 | rel << 9
+    __shared__ uint16_t order[B::TILES];         // tiles in class order
+    __shared__ uint32_t class_count[WAVES][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
     const uint32_t per = (nfull + gridDim.x - 1) / gridDim.x;
     const uint32_t first = blockIdx.x * per;
@@ -754,9 +758,28 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         tile_pos<B::TILES>(m, tid, &b, &rel, &total4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) pay[(uint32_t)i * B::TILES + tid] = pre[i];
-        const uint32_t my_s16 = s16, my_z16 = z16, my_pv = pv;
+        // Tiles are regrouped by class -- (plain | transformed) x (3 | 4 bit) -- as in the encoder: lane p decodes
+        // the p-th tile in class order, so the butterfly runs only in the wavefronts that hold transformed tiles.
+        tile_meta[tid] = make_uint2(s16 | (z16 << 16), pv | ((b == 4u) ? 0x100u : 0u) | (rel << 9));
+        const uint32_t cls = ((pv >> 7) << 1) | (b == 4u ? 1u : 0u);
+        uint32_t rank_in_wave = 0;
+#pragma unroll
+        for (uint32_t c = 0; c < 4; ++c) {
+            const uint64_t mask = __ballot(cls == c);
+            if (cls == c) rank_in_wave = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            if (lane == 0) class_count[wave][c] = (uint32_t)__popcll(mask);
+        }
         __syncthreads();
         if (have_prev) stage_out<G, ES, true>(out, (uint64_t)prev_batch * B::TILES, B::TILES, lds);
+        {
+            uint32_t pos = rank_in_wave;
+#pragma unroll
+            for (uint32_t c = 0; c < 4; ++c)
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w)
+                    if (c < cls || (c == cls && w < wave)) pos += class_count[w][c];
+            order[pos] = (uint16_t)tid;
+        }
         __syncthreads();
 
         if (batch + 1 < last) {
@@ -767,7 +790,12 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
             }
             fetch(batch + 1);
         }
-        decode_row<G, OUT_BF16>(pay + rel, b, my_s16, my_z16, my_pv, row);
+        {
+            const uint32_t t = order[tid];
+            const uint2 tm = tile_meta[t];
+            decode_row<G, OUT_BF16>(pay + (tm.y >> 9), (tm.y & 0x100u) ? 4u : 3u, tm.x & 0xffffu, tm.x >> 16, tm.y & 0xffu,
+                                    lds + t * B::STRIDE);
+        }
         prev_batch = batch;
         have_prev = true;
         __syncthreads();
