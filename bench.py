@@ -22,9 +22,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled by what
 # the same counter reads for a plain copy kernel of known size; see profiles/ for the summaries.
 TRAFFIC_BYTES = {
-    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_quant_pack"): int((264283.5 * 2.0 + 127359.0) * 1024),
-    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_entropy"): int((262239.9 * 2.0 + 16639.2) * 1024),
-    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_decode"): int((81924.4 * 2.0 + 524288.0) * 1024),
+    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_quant_pack"): int((264285.8 * 2.0 + 127357.4) * 1024),
+    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_entropy"): int((262223.7 * 2.0 + 16639.2) * 1024),
+    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_decode"): int((65621.1 * 2.0 + 524484.2) * 1024),
 }
 
 
@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (default: the metric's config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of the input tensor (known size), so that a rocprofv3 --pmc "
+                         "run of this command can scale FETCH_SIZE / WRITE_SIZE by what they read for it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this codec runs on one GPU; nothing here shards across GPUs (use --gpus 1)", file=sys.stderr)
@@ -89,6 +92,11 @@ def main():
     d_in = torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
     del x
     codec = tahq.Codec(cfg, device="cuda:0")          # decodes into the input dtype
+    if args.copy_calibration:
+        scratch = torch.empty_like(d_in)
+        scratch.copy_(d_in)                           # one elementwise copy kernel: reads and writes the tensor once
+        torch.cuda.synchronize()
+        del scratch
     T = w.elements // w.tile
     k = tahq.tahq_k_per_unit(cfg)
     n_per_unit = w.seq * (w.hidden // w.tile)
