@@ -18,12 +18,13 @@ class Cfg(C.Structure):
         ("dtype", C.c_uint32), ("scope", C.c_uint32),
         ("budget_bits", C.c_float), ("tau", C.c_float),
         ("eps_l1", C.c_float), ("eps_log", C.c_float), ("eps_ratio", C.c_float),
+        ("alloc_tile", C.c_uint32),
     ]
 
 
 def make_cfg(batch, seq, hidden, tile, dtype, budget_bits, tau=2.0, eps_l1=1e-8, eps_log=1e-8,
-             eps_ratio=1e-8, scope=0):
-    return Cfg(batch, seq, hidden, tile, dtype, scope, budget_bits, tau, eps_l1, eps_log, eps_ratio)
+             eps_ratio=1e-8, scope=0, alloc_tile=0):
+    return Cfg(batch, seq, hidden, tile, dtype, scope, budget_bits, tau, eps_l1, eps_log, eps_ratio, alloc_tile)
 
 
 _lib = None
@@ -52,6 +53,10 @@ def lib():
         L.tahq_oracle_log.argtypes = [C.c_float]
         L.tahq_oracle_entropy.restype = C.c_float
         L.tahq_oracle_entropy.argtypes = [C.c_void_p, C.c_uint32, C.c_float, C.c_float]
+        L.tahq_oracle_entropy_alloc.restype = C.c_float
+        L.tahq_oracle_entropy_alloc.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_float, C.c_float]
+        L.tahq_oracle_alloc_entropies.restype = C.c_int
+        L.tahq_oracle_alloc_entropies.argtypes = [P(Cfg), C.c_void_p, C.c_void_p]
         L.tahq_oracle_outlier.restype = C.c_int
         L.tahq_oracle_outlier.argtypes = [C.c_void_p, C.c_uint32, C.c_float, C.c_float, P(C.c_uint32)]
         L.tahq_oracle_butterfly.restype = None
@@ -91,6 +96,19 @@ def n_tiles(cfg):
     return cfg.batch * cfg.seq * (cfg.hidden // cfg.tile)
 
 
+def tiles_per_alloc(cfg):
+    return cfg.alloc_tile // cfg.tile if cfg.alloc_tile else 1
+
+
+def alloc_entropies(cfg, x):
+    """Entropy of every allocation tile (one per quantization tile when A = G)."""
+    _check_input(cfg, x)
+    H = np.empty(n_tiles(cfg) // tiles_per_alloc(cfg), np.float32)
+    rc = lib().tahq_oracle_alloc_entropies(C.byref(cfg), _ptr(x), _ptr(H))
+    assert rc == 0, rc
+    return H
+
+
 def k_per_unit(cfg):
     return int(lib().tahq_oracle_k(C.byref(cfg)))
 
@@ -113,9 +131,10 @@ def tile_stats(cfg, x):
 
 
 def allocate(cfg, H):
+    """H: one entropy per allocation tile; returns the width (3 or 4) of every quantization tile."""
     H = np.ascontiguousarray(H, np.float32)
-    assert H.size == n_tiles(cfg)
-    width = np.empty(H.size, np.uint8)
+    assert H.size == n_tiles(cfg) // tiles_per_alloc(cfg)
+    width = np.empty(n_tiles(cfg), np.uint8)
     rc = lib().tahq_oracle_allocate(C.byref(cfg), _ptr(H), _ptr(width))
     assert rc == 0, rc
     return width
@@ -169,6 +188,13 @@ def bf16_rne(x):
 def entropy(v, eps_l1=1e-8, eps_log=1e-8):
     v = np.ascontiguousarray(v, np.float32)
     return float(lib().tahq_oracle_entropy(_ptr(v), v.size, eps_l1, eps_log))
+
+
+def entropy_alloc(v, G, eps_l1=1e-8, eps_log=1e-8):
+    """Entropy of one allocation tile v of m*G channels."""
+    v = np.ascontiguousarray(v, np.float32)
+    assert v.size % G == 0
+    return float(lib().tahq_oracle_entropy_alloc(_ptr(v), G, v.size // G, eps_l1, eps_log))
 
 
 def outlier(v, tau=2.0, eps_ratio=1e-8):

@@ -43,6 +43,7 @@ typedef struct {
     float eps_l1;         /* epsilon of Eq. 1 */
     float eps_log;        /* varsigma of Eq. 2 */
     float eps_ratio;      /* varrho of Eq. 3 */
+    uint32_t alloc_tile;  /* A: allocation-tile size (Sec. 3.2), a multiple of G dividing C; 0 means A = G */
 } tahq_oracle_cfg;
 
 enum { OR_OK = 0, OR_BAD = 1, OR_SMALL = 2 };
@@ -55,7 +56,14 @@ static int cfg_ok(const tahq_oracle_cfg *c)
     if (c->hidden % c->tile) return 0;
     if (c->dtype > 1 || c->scope > 1) return 0;
     if (!(c->budget_bits >= 3.0f && c->budget_bits <= 4.0f)) return 0;
+    if (c->alloc_tile != 0 && (c->alloc_tile % c->tile || c->hidden % c->alloc_tile)) return 0;
     return 1;
+}
+
+/* m = A / G: quantization tiles per allocation tile (Sec. 3.2: A is aligned with the quantization tiles). */
+static uint32_t tiles_per_alloc(const tahq_oracle_cfg *c)
+{
+    return c->alloc_tile ? c->alloc_tile / c->tile : 1u;
 }
 
 static uint64_t n_tiles(const tahq_oracle_cfg *c)
@@ -63,19 +71,24 @@ static uint64_t n_tiles(const tahq_oracle_cfg *c)
     return (uint64_t)c->batch * c->seq * (c->hidden / c->tile);
 }
 
-/* Ranking unit: one sample (scope 0) or the whole tensor (scope 1). */
+/* Ranking unit: one sample (scope 0) or the whole tensor (scope 1).  Counted in quantization tiles. */
 static uint64_t tiles_per_unit(const tahq_oracle_cfg *c)
 {
     uint64_t n = (uint64_t)c->seq * (c->hidden / c->tile);
     return c->scope ? n * c->batch : n;
 }
+/* ... and in allocation tiles: the S*M tiles of Sec. 3.2 that are ranked. */
+static uint64_t alloc_tiles_per_unit(const tahq_oracle_cfg *c)
+{
+    return tiles_per_unit(c) / tiles_per_alloc(c);
+}
 static uint64_t n_units(const tahq_oracle_cfg *c) { return c->scope ? 1 : c->batch; }
 
-/* Sec. 3.2, top-p%: number of INT4 tiles per ranking unit.  p = budget-3, so
- * the mean payload width is 3 + k/n.  Rounded to nearest, in double. */
+/* Sec. 3.2, top-p%: number of INT4 allocation tiles per ranking unit.  p = budget-3,
+ * so the mean payload width is 3 + k/n.  Rounded to nearest, in double. */
 uint64_t tahq_oracle_k(const tahq_oracle_cfg *c)
 {
-    double n = (double)tiles_per_unit(c);
+    double n = (double)alloc_tiles_per_unit(c);
     double k = floor((double)c->budget_bits * n - 3.0 * n + 0.5);
     if (k < 0) k = 0;
     if (k > n) k = n;
@@ -202,21 +215,36 @@ static float tree_sum(float *z, uint32_t n)
     return z[0];
 }
 
-/* Eq. 1 and Eq. 2 on one raw tile.  Eq. 2 is printed without a minus sign, yet
- * the text beside it says H is high for evenly spread energy and low for a
- * sharp outlier; that fixes H = -sum p log(p+varsigma) (Shannon), natural log. */
+/* Eq. 1 and Eq. 2 on one allocation tile of m quantization tiles (A = m*G channels, Sec. 3.2; m = 1 in
+ * the default configuration A = G).  Eq. 2 is printed without a minus sign, yet the text beside it says H
+ * is high for evenly spread energy and low for a sharp outlier; that fixes H = -sum p log(p+varsigma)
+ * (Shannon), natural log.  The norm and the entropy are sums over the A channels: inside each
+ * quantization tile by the pairwise tree, and across the m tiles from left to right. */
+float tahq_oracle_entropy_alloc(const float *v, uint32_t G, uint32_t m, float eps_l1, float eps_log)
+{
+    float w[128];
+    float L1 = 0.0f;
+    for (uint32_t q = 0; q < m; ++q) {
+        for (uint32_t k = 0; k < G; ++k) w[k] = fabsf(v[q * G + k]);
+        L1 = L1 + tree_sum(w, G);
+    }
+    float invL = 1.0f / (L1 + eps_l1);
+    float W = 0.0f;
+    for (uint32_t q = 0; q < m; ++q) {
+        for (uint32_t k = 0; k < G; ++k) {
+            float p = fabsf(v[q * G + k]) * invL;
+            float u = p + eps_log;
+            w[k] = p * tahq_oracle_log(u);
+        }
+        W = W + tree_sum(w, G);
+    }
+    return 0.0f - W;
+}
+
+/* The default A = G: the allocation tile is the quantization tile. */
 float tahq_oracle_entropy(const float *v, uint32_t G, float eps_l1, float eps_log)
 {
-    float a[128], w[128];
-    for (uint32_t k = 0; k < G; ++k) { a[k] = fabsf(v[k]); w[k] = a[k]; }
-    float L1 = tree_sum(w, G);
-    float invL = 1.0f / (L1 + eps_l1);
-    for (uint32_t k = 0; k < G; ++k) {
-        float p = a[k] * invL;
-        float u = p + eps_log;
-        w[k] = p * tahq_oracle_log(u);
-    }
-    return 0.0f - tree_sum(w, G);
+    return tahq_oracle_entropy_alloc(v, G, 1, eps_l1, eps_log);
 }
 
 /* Eq. 3: pivot index d (lowest index among equal maxima), and whether the
@@ -370,7 +398,7 @@ static void make_layout(const tahq_oracle_cfg *c, layout *L)
     L->scale = L->pivot + pad64(T);
     L->zero = L->scale + pad64(2 * T);
     L->payload = L->zero + pad64(2 * T);
-    L->total = L->payload + (uint64_t)(c->tile / 8) * (3 * T + n_units(c) * k);
+    L->total = L->payload + (uint64_t)(c->tile / 8) * (3 * T + n_units(c) * k * tiles_per_alloc(c));
 }
 
 uint64_t tahq_oracle_packed_size(const tahq_oracle_cfg *c)
@@ -408,6 +436,7 @@ static void write_header(const tahq_oracle_cfg *c, uint8_t *p)
     put_u32(p + 44, f32_bits(c->eps_l1));
     put_u32(p + 48, f32_bits(c->eps_log));
     put_u32(p + 52, f32_bits(c->eps_ratio));
+    put_u32(p + 56, c->alloc_tile ? c->alloc_tile : c->tile);
 }
 
 /* --------------------------------------------------------- bit allocation */
@@ -422,21 +451,40 @@ static int by_entropy_desc_then_index(const void *pa, const void *pb)
     return (a->j > b->j) - (a->j < b->j);
 }
 
-/* Sec. 3.2, top-p% tile selection: inside each ranking unit the k tiles of
- * highest entropy get 4 bits, the rest 3; equal entropies go to the lower tile
- * index.  width[j] receives 3 or 4. */
+/* Sec. 3.2, top-p% tile selection: inside each ranking unit the k allocation tiles of highest entropy
+ * get 4 bits, the rest 3; equal entropies go to the lower tile index.  H has one entry per allocation
+ * tile; width[j] receives 3 or 4 for every QUANTIZATION tile j (the m tiles of an allocation tile share
+ * its width). */
 int tahq_oracle_allocate(const tahq_oracle_cfg *c, const float *H, uint8_t *width)
 {
     if (!cfg_ok(c)) return OR_BAD;
-    uint64_t n = tiles_per_unit(c), U = n_units(c), k = tahq_oracle_k(c);
+    uint64_t n = alloc_tiles_per_unit(c), U = n_units(c), k = tahq_oracle_k(c);
+    uint32_t m = tiles_per_alloc(c);
     rank_item *it = (rank_item *)malloc((size_t)n * sizeof *it);
     if (!it) return OR_BAD;
     for (uint64_t u = 0; u < U; ++u) {
         for (uint64_t j = 0; j < n; ++j) { it[j].H = H[u * n + j]; it[j].j = j; }
         qsort(it, (size_t)n, sizeof *it, by_entropy_desc_then_index);
-        for (uint64_t r = 0; r < n; ++r) width[u * n + it[r].j] = (r < k) ? 4 : 3;
+        for (uint64_t r = 0; r < n; ++r)
+            for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (r < k) ? 4 : 3;
     }
     free(it);
+    return OR_OK;
+}
+
+/* Entropy of every allocation tile (T/m values). */
+int tahq_oracle_alloc_entropies(const tahq_oracle_cfg *c, const void *in, float *H)
+{
+    if (!cfg_ok(c) || !in || !H) return OR_BAD;
+    uint64_t T = n_tiles(c);
+    uint32_t G = c->tile, m = tiles_per_alloc(c);
+    float *v = (float *)malloc((size_t)m * G * sizeof(float));
+    if (!v) return OR_BAD;
+    for (uint64_t ja = 0; ja < T / m; ++ja) {
+        for (uint32_t q = 0; q < m; ++q) load_tile(c, in, ja * m + q, v + q * G);
+        H[ja] = tahq_oracle_entropy_alloc(v, G, m, c->eps_l1, c->eps_log);
+    }
+    free(v);
     return OR_OK;
 }
 
@@ -473,13 +521,10 @@ int tahq_oracle_encode(const tahq_oracle_cfg *c, const void *in, uint8_t *packed
     uint8_t *width = (uint8_t *)malloc((size_t)T);
     if (!H || !width) { free(H); free(width); return OR_BAD; }
 
-    /* pass 1: entropies (Eq. 1-2) */
+    /* pass 1: entropies of the allocation tiles (Eq. 1-2) */
     float v[128], y[128];
     tile_rec r;
-    for (uint64_t j = 0; j < T; ++j) {
-        load_tile(c, in, j, v);
-        H[j] = tahq_oracle_entropy(v, G, c->eps_l1, c->eps_log);
-    }
+    if (tahq_oracle_alloc_entropies(c, in, H) != OR_OK) { free(H); free(width); return OR_BAD; }
     /* top-p% selection */
     tahq_oracle_allocate(c, H, width);
 

@@ -15,8 +15,16 @@ import test_oracle_pins as pins
 SRC = open(build_oracle.SRC).read()
 
 MUTATIONS = [
-    ("entropy without the Shannon minus sign", "return 0.0f - tree_sum(w, G);", "return tree_sum(w, G);"),
-    ("entropy of unnormalized magnitudes", "float p = a[k] * invL;", "float p = a[k];"),
+    ("entropy without the Shannon minus sign", "return 0.0f - W;", "return W;"),
+    ("entropy of unnormalized magnitudes", "float p = fabsf(v[q * G + k]) * invL;", "float p = fabsf(v[q * G + k]);"),
+    ("allocation tile normalised per quantization tile", "        L1 = L1 + tree_sum(w, G);\n    }\n    float invL = 1.0f / (L1 + eps_l1);\n    float W = 0.0f;\n    for (uint32_t q = 0; q < m; ++q) {\n",
+     "        L1 = L1 + tree_sum(w, G);\n    }\n    float invL = 1.0f / (L1 + eps_l1);\n    float W = 0.0f;\n    for (uint32_t q = 0; q < m; ++q) {\n        for (uint32_t k = 0; k < G; ++k) w[k] = fabsf(v[q * G + k]);\n        invL = 1.0f / (tree_sum(w, G) + eps_l1);\n"),
+    ("allocation tile entropy keeps only its last quantization tile", "W = W + tree_sum(w, G);", "W = tree_sum(w, G);"),
+    ("allocation tile norm keeps only its last quantization tile", "L1 = L1 + tree_sum(w, G);", "L1 = tree_sum(w, G);"),
+    ("k counted over quantization tiles", "double n = (double)alloc_tiles_per_unit(c);", "double n = (double)tiles_per_unit(c);"),
+    ("width written to the first quantization tile of an allocation tile only",
+     "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (r < k) ? 4 : 3;",
+     "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (r < k && q == 0) ? 4 : 3;"),
     ("log polynomial coefficient off by 2x", "0x1.c4859ep+2f", "0x1.c4859ep+1f"),
     ("butterfly difference with swapped operands", "v[j + h] = x - y;", "v[j + h] = y - x;"),
     ("wrong 1/sqrt(G) for G = 64", "(G == 64 ? 0.125f :", "(G == 64 ? 0.25f :"),

@@ -356,6 +356,109 @@ def test_allocation_matches_lexsort_on_random_entropies_with_duplicates():
     assert np.array_equal(o32.allocate(cfg, H), o64.allocate(H, 3, o32.k_per_unit(cfg)))
 
 
+# ------------------------------------- allocation tiles larger than G
+
+@pytest.mark.parametrize("G,m", [(32, 2), (64, 3), (64, 16), (128, 64)])
+def test_allocation_tile_entropy_closed_forms_and_float64_definition(G, m):
+    # Sec. 3.2, Eq. 1-2 on A = m*G channels: uniform magnitudes -> ln A; one-hot -> 0; j equal entries -> ln j.
+    A = G * m
+    tol = 3e-5 * max(1.0, math.log(A))
+    assert abs(o32.entropy_alloc(np.full(A, -0.75, np.float32), G) - math.log(A)) < tol
+    onehot = np.zeros(A, np.float32); onehot[A - 3] = 9.0
+    assert abs(o32.entropy_alloc(onehot, G)) < tol
+    assert o32.entropy_alloc(np.zeros(A, np.float32), G) == 0.0
+    for j in (2, G, G + 1, A // 2):
+        v = np.zeros(A, np.float32); v[np.linspace(0, A - 1, j).astype(int)] = 3.0
+        assert abs(o32.entropy_alloc(v, G) - math.log(j)) < tol
+    rng = np.random.default_rng(31)
+    v = rng.standard_normal((20, A)).astype(np.float32) * np.exp(rng.standard_normal((20, A))).astype(np.float32)
+    want = o64.entropy(v)
+    got = np.array([o32.entropy_alloc(t, G) for t in v])
+    assert np.max(np.abs(got - want)) < tol
+    # the split into quantization tiles only fixes the rounding order
+    if A <= 128:
+        assert np.max(np.abs(got - np.array([o32.entropy(t) for t in v]))) < tol
+
+
+def test_allocation_tile_of_one_quantization_tile_is_the_default():
+    rng = np.random.default_rng(32)
+    for G in (32, 64, 128):
+        for t in rng.standard_normal((50, G)).astype(np.float32):
+            assert o32.entropy_alloc(t, G) == o32.entropy(t)
+    w, x = workloads.generate(2, batch=2, seq=24)
+    a = o32.encode(o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.4), x)
+    b = o32.encode(o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.4, alloc_tile=w.tile), x)
+    assert np.array_equal(a, b)
+    assert a[:64].view("<u4")[14] == w.tile
+
+
+@pytest.mark.parametrize("index,shape,m", [(1, dict(batch=2, seq=12), 2), (2, dict(batch=2, seq=24), 4),
+                                           (4, dict(batch=2, seq=10), 8), (5, dict(batch=1, seq=16), 5)])
+def test_allocation_over_tiles_of_several_quantization_tiles(index, shape, m):
+    w, x = workloads.generate(index, **shape)
+    G, A = w.tile, w.tile * m
+    assert w.hidden % A == 0
+    cfg = o32.make_cfg(w.batch, w.seq, w.hidden, G, w.dtype, 3.3, alloc_tile=A)
+    T = o32.n_tiles(cfg)
+    nA = w.seq * (w.hidden // A)
+    kA = o32.k_per_unit(cfg)
+    assert kA == o64.k_per_unit(nA, 3.3)
+    packed = o32.encode(cfg, x)
+    assert packed.size == o32.packed_size(cfg) == o64.section_offsets(T, G, w.batch, kA * m)["total"]
+    out64, s = o64.decode_stream(packed, T, G, w.batch, kA * m)
+    hdr = s["header"].view("<u4")
+    assert list(hdr[1:9]) == [1, w.dtype, w.batch, w.seq, w.hidden, G, 0, kA] and hdr[14] == A
+    # entropies of the allocation tiles against the float64 definition on A channels
+    xf = (x if w.dtype == workloads.F32 else workloads.bf16_bits_to_f32(x)).astype(np.float64)
+    HA = o32.alloc_entropies(cfg, x)
+    assert HA.shape == (w.batch * nA,)
+    assert np.max(np.abs(HA - o64.entropy(xf.reshape(-1, A)))) < 5e-5
+    # one width per allocation tile: the top kA of each sample, shared by its m quantization tiles
+    wantA = o64.allocate(HA, w.batch, kA)
+    assert np.array_equal(s["width"], np.repeat(wantA, m))
+    assert np.array_equal(o32.allocate(cfg, HA), np.repeat(wantA, m))
+    assert np.array_equal(s["ranks"], s["rank_of"][::64])
+    # quantization is untouched by A: pivots and ranges are those of the quantization tiles
+    _, pivot, mn, mx = o32.tile_stats(cfg, x)
+    assert np.array_equal(s["pivot"], pivot)
+    sf = s["scale"].astype(np.float64); zf = s["zero"].astype(np.float64)
+    L = (1 << s["width"]) - 1
+    assert np.all(zf <= mn) and np.all(zf + L * sf >= mx) and np.all(s["codes"] <= L[:, None])
+    out32 = o32.decode(cfg, packed, o32.F32).reshape(T, G).astype(np.float64)
+    scale = np.maximum(np.abs(out64).max(axis=1, keepdims=True), 1e-30)
+    assert np.max(np.abs(out32 - out64) / scale) < 1e-5
+    err = np.linalg.norm(out64 - xf.reshape(T, G), axis=1)
+    assert np.all(err <= sf / 2 * math.sqrt(G) * (1 + 1e-3) + 1e-6 * np.abs(xf.reshape(T, G)).max(axis=1))
+
+
+def test_token_level_allocation_is_the_special_case_A_equals_C():
+    # Sec. 3.2: with A = C every allocation tile is a whole token, so a token's tiles share one width and
+    # the INT4 tokens are the top-p% of the per-token entropies.
+    w, x = workloads.generate(2, batch=2, seq=40)
+    G, Cc = w.tile, w.hidden
+    cfg = o32.make_cfg(w.batch, w.seq, Cc, G, w.dtype, 3.25, alloc_tile=Cc)
+    assert o32.k_per_unit(cfg) == 10
+    s = o64.parse_stream(o32.encode(cfg, x), o32.n_tiles(cfg), G, w.batch, 10 * (Cc // G))
+    per_token = s["width"].reshape(w.batch, w.seq, Cc // G)
+    assert np.all(per_token == per_token[:, :, :1])
+    xf = (x if w.dtype == workloads.F32 else workloads.bf16_bits_to_f32(x)).astype(np.float64)
+    Htok = o64.entropy(xf.reshape(-1, Cc)).reshape(w.batch, w.seq)
+    for i in range(w.batch):
+        chosen = set(np.nonzero(per_token[i, :, 0] == 4)[0])
+        order = np.argsort(-Htok[i], kind="stable")
+        # float64 ranking agrees wherever the gap at the cut is above the fp32 evaluation error
+        sure_in = {int(t) for t in order[:10] if Htok[i, t] - Htok[i, order[10]] > 1e-4}
+        sure_out = {int(t) for t in order[10:] if Htok[i, order[9]] - Htok[i, t] > 1e-4}
+        assert len(chosen) == 10 and sure_in <= chosen and not (sure_out & chosen)
+
+
+def test_allocation_tile_must_align_with_quantization_tiles_and_divide_the_hidden_size():
+    assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=96)) == 0     # not a multiple of G
+    assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=256)) == 0    # does not divide C
+    assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=32)) == 0     # below G
+    assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=192)) > 0
+
+
 # -------------------------------------------------------------- format
 
 def test_packed_size_closed_form_and_survey_table():
