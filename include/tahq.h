@@ -12,6 +12,9 @@
  *     transform (1/sqrt(G)) H_G                               [Sec. 3.3, Eq. 4]
  *   - 3- or 4-bit width: the top-p% highest-entropy tiles of
  *     every sample get 4 bits, p = budget_bits - 3            [Sec. 3.2]
+ *     (entropy and ranking may run on allocation tiles of
+ *     A = alloc_tile channels, A a multiple of `tile`; the
+ *     quantization tiles inside one share its width)
  *   - asymmetric uniform quantization with a per-tile scale
  *     and zero-point                                          [Sec. 3.1, 3.3]
  *   - packing of codes and metadata into one uint8 stream     [Sec. 3.4]
@@ -31,9 +34,9 @@
  *   - A failed launch is reported as TAHQ_ERR_HIP (hipGetLastError is consumed).
  *
  * Stream layout (little-endian; every section padded to 64 bytes), T = number
- * of tiles = batch*seq*hidden/tile, k = 4-bit tiles per ranking unit:
+ * of tiles = batch*seq*hidden/tile, k = 4-bit allocation tiles per ranking unit:
  *   header   64 B   "TAHQ", version, dtype, batch, seq, hidden, tile, scope, k,
- *                   budget, tau, eps_l1, eps_log, eps_ratio (32-bit words), zeros
+ *                   budget, tau, eps_l1, eps_log, eps_ratio, A (32-bit words), zero
  *   bitmap   T bits         tile j -> byte j>>3, bit j&7; 1 = 4-bit tile
  *   ranks    uint32[ceil(T/64)]   4-bit tiles before each group of 64 tiles
  *   pivot    uint8[T]       bit 7 = tile was transformed, bits 0..6 = pivot index d
@@ -59,7 +62,8 @@ typedef void *tahq_stream;
 typedef enum {
     TAHQ_OK = 0,
     TAHQ_ERR_NULL = 1,                 /* a required pointer is NULL                     */
-    TAHQ_ERR_INVALID_ARG = 2,          /* zero dimension, hidden % tile != 0, budget outside [3,4] or NaN, bad enum */
+    TAHQ_ERR_INVALID_ARG = 2,          /* zero dimension, hidden % tile != 0, alloc_tile not a multiple of tile dividing hidden,
+                                          budget outside [3,4] or NaN, bad enum */
     TAHQ_ERR_UNSUPPORTED = 3,          /* tile not in {32, 64, 128}, or more than 2^31 tiles */
     TAHQ_ERR_BUFFER_TOO_SMALL = 4,     /* packed capacity / packed_bytes below tahq_packed_size */
     TAHQ_ERR_WORKSPACE_TOO_SMALL = 5,  /* workspace capacity below tahq_workspace_size   */
@@ -70,11 +74,12 @@ typedef enum {
 typedef enum { TAHQ_F32 = 0, TAHQ_BF16 = 1 } tahq_dtype;
 
 typedef struct {
-    uint32_t struct_size;   /* = sizeof(tahq_config); set by tahq_config_default                 */
+    uint32_t struct_size;   /* = sizeof(tahq_config); set by tahq_config_default.  48 (a caller built
+                               before alloc_tile existed) is accepted and means alloc_tile = 0      */
     uint32_t batch;         /* B                                                                  */
     uint32_t seq;           /* S                                                                  */
     uint32_t hidden;        /* C; tensor is contiguous row-major [B, S, C]                        */
-    uint32_t tile;          /* G = A (quantization tile = allocation tile, the paper's default): 32, 64 or 128 */
+    uint32_t tile;          /* G, the quantization tile: 32, 64 or 128                            */
     uint32_t dtype;         /* tahq_dtype of the activation tensor                                */
     uint32_t scope;         /* 0 = rank the tiles of every sample (the paper); 1 = rank the whole tensor */
     float budget_bits;      /* mean payload bits per element, in [3.0, 4.0]                       */
@@ -82,14 +87,16 @@ typedef struct {
     float eps_l1;           /* epsilon of Eq. 1;   default 1e-8                                   */
     float eps_log;          /* varsigma of Eq. 2;  default 1e-8                                   */
     float eps_ratio;        /* varrho of Eq. 3;    default 1e-8                                   */
+    uint32_t alloc_tile;    /* A, the allocation tile of Sec. 3.2: a multiple of G that divides C;
+                               0 = G (the paper's default); A = C is token-level allocation        */
 } tahq_config;
 
 /* Fill *cfg with the defaults (tile 64, budget 3.8, tau 2.0, eps 1e-8, scope 0,
  * dtype bf16, dimensions 0).  cfg: host, written.  No error: NULL is ignored. */
 void tahq_config_default(tahq_config *cfg);
 
-/* Number of 4-bit tiles per ranking unit: round((budget_bits - 3) * n) with n
- * the tiles of one sample (scope 0) or of the tensor (scope 1)  [Sec. 3.2, top-p%].
+/* Number of 4-bit allocation tiles per ranking unit: round((budget_bits - 3) * n) with n
+ * the allocation tiles of one sample (scope 0) or of the tensor (scope 1)  [Sec. 3.2, top-p%].
  * Returns 0 for an invalid cfg (a valid cfg with budget 3.0 also gives 0). */
 uint64_t tahq_k_per_unit(const tahq_config *cfg);
 
@@ -144,10 +151,19 @@ tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t pac
                         tahq_stream stream);
 
 /* Intermediates of the encoder, for tests and profiling  [Sec. 3.2 Eq. 1-2].
- *   d_entropy   device, written: float[T], the entropy of every raw tile
+ *   d_entropy   device, written: float[T], the entropy of every raw quantization tile
+ *               (cfg->alloc_tile is ignored: the result is that of A = G)
  * Same validation as tahq_encode. */
 tahq_status tahq_tile_entropy(const tahq_config *cfg, const void *d_in, float *d_entropy,
                               tahq_stream stream);
+
+/* Entropy of every allocation tile of A = cfg->alloc_tile channels  [Sec. 3.2 Eq. 1-2 on
+ * the reshaped tensor B x (S*C/A) x A]: the values the encoder ranks.
+ *   d_entropy   device, written: float[B*S*C/A]
+ *   d_workspace device, scratch: tahq_workspace_size(cfg) bytes (used only when A > G)
+ * Same validation as tahq_encode. */
+tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, float *d_entropy,
+                                    void *d_workspace, size_t workspace_capacity, tahq_stream stream);
 
 /* Parse the 64-byte header of a stream that was copied to the host.
  *   header64    host, read: the first 64 bytes of a stream

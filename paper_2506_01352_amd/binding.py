@@ -21,6 +21,7 @@ class tahq_config(C.Structure):
         ("tile", C.c_uint32), ("dtype", C.c_uint32), ("scope", C.c_uint32),
         ("budget_bits", C.c_float), ("tau", C.c_float),
         ("eps_l1", C.c_float), ("eps_log", C.c_float), ("eps_ratio", C.c_float),
+        ("alloc_tile", C.c_uint32),
     ]
 
 
@@ -58,6 +59,8 @@ def _load():
     L.tahq_decode.argtypes = [P, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tahq_tile_entropy.restype = C.c_int
     L.tahq_tile_entropy.argtypes = [P, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.tahq_alloc_tile_entropy.restype = C.c_int
+    L.tahq_alloc_tile_entropy.argtypes = [P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tahq_parse_header.restype = C.c_int
     L.tahq_parse_header.argtypes = [C.c_void_p, P]
     L.tahq_status_string.restype = C.c_char_p
@@ -75,8 +78,9 @@ def tahq_config_default():
 
 
 def make_config(batch, seq, hidden, tile, dtype, budget_bits, tau=2.0, eps_l1=1e-8, eps_log=1e-8,
-                eps_ratio=1e-8, scope=0):
+                eps_ratio=1e-8, scope=0, alloc_tile=0):
     cfg = tahq_config_default()
+    cfg.alloc_tile = alloc_tile
     cfg.batch, cfg.seq, cfg.hidden, cfg.tile = batch, seq, hidden, tile
     cfg.dtype, cfg.scope = dtype, scope
     cfg.budget_bits, cfg.tau = budget_bits, tau
@@ -159,6 +163,13 @@ def tahq_tile_entropy(cfg, d_in, d_entropy, stream=None):
     rc = _load().tahq_tile_entropy(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_entropy), _stream_handle(stream))
     if rc != 0:
         raise TahqError(rc, "tahq_tile_entropy")
+
+
+def tahq_alloc_tile_entropy(cfg, d_in, d_entropy, d_workspace, stream=None):
+    rc = _load().tahq_alloc_tile_entropy(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_entropy), _dev_ptr(d_workspace),
+                                         _nbytes(d_workspace), _stream_handle(stream))
+    if rc != 0:
+        raise TahqError(rc, "tahq_alloc_tile_entropy")
 
 
 def tahq_parse_header(header_bytes):

@@ -90,6 +90,26 @@ struct LaunchDecode {
     }
 };
 
+template <int G, bool BF16>
+struct LaunchAllocEntropy {
+    // Entropies of allocation tiles of m > 1 quantization tiles: two streaming passes over the tensor.
+    static void run(const void *d_in, float *d_H, float *part, float *inv_norm, uint32_t T, uint32_t m, float eps_l1,
+                    float eps_log, hipStream_t st)
+    {
+        using B = Batch<G, BF16 ? 2 : 4>;
+        const uint32_t nb = (T + B::TILES - 1) / B::TILES;
+        const uint32_t n_alloc = T / m;
+        hipLaunchKernelGGL((k_tile_partial<G, BF16, false>), dim3(nb), dim3(B::TILES), 0, st, d_in,
+                           (const float *)nullptr, part, T, m, eps_log);
+        hipLaunchKernelGGL((k_alloc_reduce<false>), dim3(blocks_for(n_alloc)), dim3(256), 0, st, (const float *)part,
+                           inv_norm, n_alloc, m, eps_l1);
+        hipLaunchKernelGGL((k_tile_partial<G, BF16, true>), dim3(nb), dim3(B::TILES), 0, st, d_in,
+                           (const float *)inv_norm, part, T, m, eps_log);
+        hipLaunchKernelGGL((k_alloc_reduce<true>), dim3(blocks_for(n_alloc)), dim3(256), 0, st, (const float *)part,
+                           d_H, n_alloc, m, eps_l1);
+    }
+};
+
 // Returns true if the first-digit histogram was built along the way.
 bool launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, uint32_t *hist0,
                     hipStream_t st)
@@ -126,7 +146,7 @@ uint64_t tahq_k_per_unit(const tahq_config *cfg)
 {
     Shape s;
     if (make_shape(cfg, &s) != TAHQ_OK) return 0;
-    return s.k;
+    return s.kA;
 }
 
 size_t tahq_packed_size(const tahq_config *cfg)
@@ -158,6 +178,31 @@ tahq_status tahq_tile_entropy(const tahq_config *cfg, const void *d_in, float *d
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
 
+tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, float *d_entropy, void *d_workspace,
+                                    size_t workspace_capacity, tahq_stream stream)
+{
+    Shape s;
+    tahq_status rc = make_shape(cfg, &s);
+    if (rc != TAHQ_OK) return rc;
+    if (!d_in || !d_entropy) return TAHQ_ERR_NULL;
+    if (misaligned(d_in) || misaligned(d_entropy)) return TAHQ_ERR_MISALIGNED;
+    if (s.m == 1) {
+        launch_entropy(s, cfg, d_in, d_entropy, nullptr, (hipStream_t)stream);
+    } else {
+        if (!d_workspace) return TAHQ_ERR_NULL;
+        Workspace ws;
+        make_workspace(s, &ws);
+        if (workspace_capacity < ws.total) return TAHQ_ERR_WORKSPACE_TOO_SMALL;
+        if (misaligned(d_workspace)) return TAHQ_ERR_MISALIGNED;
+        uint8_t *wsb = static_cast<uint8_t *>(d_workspace);
+        dispatch<LaunchAllocEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_entropy,
+                                     reinterpret_cast<float *>(wsb + ws.part),
+                                     reinterpret_cast<float *>(wsb + ws.inv_norm), (uint32_t)s.T, s.m, cfg->eps_l1,
+                                     cfg->eps_log, (hipStream_t)stream);
+    }
+    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+}
+
 tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d_packed, size_t packed_capacity,
                                void *d_workspace, size_t workspace_capacity, uint32_t phases, tahq_stream stream)
 {
@@ -179,7 +224,8 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     uint8_t *wsb = static_cast<uint8_t *>(d_workspace);
     uint64_t *bitmap = reinterpret_cast<uint64_t *>(packed + lay.bitmap);
     uint32_t *ranks = reinterpret_cast<uint32_t *>(packed + lay.ranks);
-    const bool select = s.k != 0 && s.k != s.n;
+    const bool select = s.kA != 0 && s.kA != s.nA;
+    const bool wide = s.m > 1;     // allocation tiles of several quantization tiles
 
     // header, section padding, selection scratch
     HeaderWords hdr;
@@ -187,7 +233,8 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     hdr.w[0] = 0x51484154u;   // "TAHQ"
     hdr.w[1] = 1;
     hdr.w[2] = s.dtype; hdr.w[3] = s.B; hdr.w[4] = s.S; hdr.w[5] = s.C; hdr.w[6] = s.G; hdr.w[7] = s.scope;
-    hdr.w[8] = (uint32_t)s.k;
+    hdr.w[8] = (uint32_t)s.kA;
+    hdr.w[14] = s.A;
     memcpy(&hdr.w[9], &cfg->budget_bits, 4);
     memcpy(&hdr.w[10], &cfg->tau, 4);
     memcpy(&hdr.w[11], &cfg->eps_l1, 4);
@@ -214,10 +261,18 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
         uint8_t *sel = wsb + ws.sel;
         // the entropy kernel builds the first-digit histogram itself when units are whole batches
         bool fused = false;
-        dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
-        if (phases & TAHQ_PHASE_ENTROPY) launch_entropy(s, cfg, d_in, H, hist0, st);
+        if (!wide) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
+        if (phases & TAHQ_PHASE_ENTROPY) {
+            if (wide)
+                dispatch<LaunchAllocEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, H, reinterpret_cast<float *>(wsb + ws.part),
+                                             reinterpret_cast<float *>(wsb + ws.inv_norm), (uint32_t)s.T, s.m,
+                                             cfg->eps_l1, cfg->eps_log, st);
+            else
+                launch_entropy(s, cfg, d_in, H, hist0, st);
+        }
         if (phases & TAHQ_PHASE_SELECT) {
-            const uint32_t n32 = (uint32_t)s.n, k32 = (uint32_t)s.k;
+            // the selection ranks allocation tiles; with A = G they are the stream's tiles
+            const uint32_t n32 = (uint32_t)s.nA, k32 = (uint32_t)s.kA;
             const dim3 rgrid(ws.hb, s.U);
             if (!fused)
                 hipLaunchKernelGGL((k_radix_pass<0, 8>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
@@ -226,16 +281,21 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
             const uint32_t sb = (ws.nseg + 3) / 4;
             hipLaunchKernelGGL(k_seg_count, dim3(sb, s.U), dim3(256), 0, st, (const float *)H, n32, ws.nseg,
                                (const uint32_t *)coarse, (const uint32_t *)partial, ws.hb, state, seg);
-            const int aligned = (s.n % 64 == 0) ? 1 : 0;
+            const int aligned = (!wide && s.n % 64 == 0) ? 1 : 0;
+            uint32_t *ranks_a = reinterpret_cast<uint32_t *>(wsb + ws.ranks_a);
             hipLaunchKernelGGL(k_assign, dim3(sb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, ws.nseg,
-                               (const uint32_t *)state, (const uint32_t *)seg, bitmap, ranks, sel, aligned);
-            if (!aligned)
+                               (const uint32_t *)state, (const uint32_t *)seg, bitmap, wide ? ranks_a : ranks, sel,
+                               aligned);
+            if (wide)
+                hipLaunchKernelGGL(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                                   (const uint8_t *)sel, (const uint32_t *)ranks_a, (uint32_t)s.T, s.m, bitmap, ranks);
+            else if (!aligned)
                 hipLaunchKernelGGL(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
                                    (const uint8_t *)sel, (uint32_t)s.T, bitmap);
         }
     } else if (phases & TAHQ_PHASE_SELECT) {
         hipLaunchKernelGGL(k_bitmap_const, dim3(blocks_for(words64)), dim3(256), 0, st, (uint32_t)s.T,
-                           s.k == s.n ? 1 : 0, bitmap, ranks);
+                           s.kA == s.nA ? 1 : 0, bitmap, ranks);
     }
 
     if (phases & TAHQ_PHASE_QUANT) {
@@ -284,10 +344,11 @@ tahq_status tahq_parse_header(const void *header64, tahq_config *cfg)
     memcpy(&cfg->eps_l1, &w[11], 4);
     memcpy(&cfg->eps_log, &w[12], 4);
     memcpy(&cfg->eps_ratio, &w[13], 4);
+    cfg->alloc_tile = w[14];
     Shape s;
     tahq_status rc = make_shape(cfg, &s);
     if (rc != TAHQ_OK) return rc;
-    return s.k == w[8] ? TAHQ_OK : TAHQ_ERR_INVALID_ARG;
+    return s.kA == w[8] ? TAHQ_OK : TAHQ_ERR_INVALID_ARG;
 }
 
 const char *tahq_status_string(tahq_status s)

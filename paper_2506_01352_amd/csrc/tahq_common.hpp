@@ -13,10 +13,14 @@ namespace tahq {
 
 struct Shape {
     uint32_t B, S, C, G, dtype, scope;
-    uint64_t T;   // tiles in the tensor
-    uint64_t n;   // tiles per ranking unit
+    uint32_t A;   // allocation tile (Sec. 3.2), a multiple of G
+    uint32_t m;   // quantization tiles per allocation tile, A / G
+    uint64_t T;   // quantization tiles in the tensor
+    uint64_t n;   // quantization tiles per ranking unit
     uint32_t U;   // ranking units
-    uint64_t k;   // 4-bit tiles per ranking unit
+    uint64_t k;   // 4-bit quantization tiles per ranking unit, m * kA
+    uint64_t nA;  // allocation tiles per ranking unit: what the selection ranks
+    uint64_t kA;  // 4-bit allocation tiles per ranking unit
 };
 
 struct Layout {
@@ -37,7 +41,10 @@ struct Workspace {
     uint64_t partial;    // uint32[U][2][hb][kHistBins]: per-workgroup histograms of digits 1, 2
     uint64_t keys;       // float[T] entropies
     uint64_t seg;        // uint32[U][nseg][2]: keys equal to / above the threshold, per segment
-    uint64_t sel;        // uint8[T] (only when n % 64 != 0)
+    uint64_t sel;        // uint8[T] (only when n % 64 != 0, or A > G)
+    uint64_t part;       // float[T]: per-quantization-tile partial sums            (only when A > G)
+    uint64_t inv_norm;   // float[T/m]: 1 / (L1 norm + eps) of every allocation tile (only when A > G)
+    uint64_t ranks_a;    // uint32[ceil(U*nA/64)]: rank table over allocation tiles  (only when A > G)
     uint64_t total;
     uint32_t nseg;       // segments per ranking unit
     uint32_t hb;         // workgroups per ranking unit in the radix passes
@@ -49,11 +56,14 @@ inline uint64_t pad256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 tahq_status make_shape(const tahq_config *c, Shape *s)
 {
     if (!c) return TAHQ_ERR_NULL;
-    if (c->struct_size != sizeof(tahq_config)) return TAHQ_ERR_INVALID_ARG;
+    // a 48-byte struct is the layout from before alloc_tile was added
+    if (c->struct_size != sizeof(tahq_config) && c->struct_size != 48u) return TAHQ_ERR_INVALID_ARG;
+    const uint32_t A = (c->struct_size == 48u || c->alloc_tile == 0) ? c->tile : c->alloc_tile;
     if (c->batch == 0 || c->seq == 0 || c->hidden == 0) return TAHQ_ERR_INVALID_ARG;
     if (c->tile == 0 || c->hidden % c->tile != 0) return TAHQ_ERR_INVALID_ARG;
     if (c->dtype > TAHQ_BF16 || c->scope > 1) return TAHQ_ERR_INVALID_ARG;
     if (!(c->budget_bits >= 3.0f && c->budget_bits <= 4.0f)) return TAHQ_ERR_INVALID_ARG;
+    if (A % c->tile != 0 || c->hidden % A != 0) return TAHQ_ERR_INVALID_ARG;
     if (c->tile != 32 && c->tile != 64 && c->tile != 128) return TAHQ_ERR_UNSUPPORTED;
     uint64_t M = c->hidden / c->tile;
     uint64_t T = (uint64_t)c->batch * c->seq * M;
@@ -61,13 +71,17 @@ tahq_status make_shape(const tahq_config *c, Shape *s)
     s->B = c->batch; s->S = c->seq; s->C = c->hidden; s->G = c->tile;
     s->dtype = c->dtype; s->scope = c->scope;
     s->T = T;
+    s->A = A;
+    s->m = A / c->tile;
     s->n = c->scope ? T : (uint64_t)c->seq * M;
     s->U = c->scope ? 1u : c->batch;
-    double n = (double)s->n;
+    s->nA = s->n / s->m;
+    double n = (double)s->nA;
     double k = __builtin_floor((double)c->budget_bits * n - 3.0 * n + 0.5);
     if (k < 0) k = 0;
     if (k > n) k = n;
-    s->k = (uint64_t)k;
+    s->kA = (uint64_t)k;
+    s->k = s->kA * s->m;
     return TAHQ_OK;
 }
 
@@ -84,8 +98,8 @@ void make_layout(const Shape &s, Layout *L)
 
 void make_workspace(const Shape &s, Workspace *w)
 {
-    w->nseg = (uint32_t)((s.n + kSegTiles - 1) / kSegTiles);
-    uint64_t hb = (s.n + kRadixKeysPerBlock - 1) / kRadixKeysPerBlock;
+    w->nseg = (uint32_t)((s.nA + kSegTiles - 1) / kSegTiles);
+    uint64_t hb = (s.nA + kRadixKeysPerBlock - 1) / kRadixKeysPerBlock;
     w->hb = (uint32_t)(hb > 64 ? 64 : hb);
     uint64_t off = 0;
     w->hist0 = off;  off += (uint64_t)s.U * kDigit0Bins * 4;
@@ -97,6 +111,13 @@ void make_workspace(const Shape &s, Workspace *w)
     w->keys = off;  off = pad256(off + s.T * 4);
     w->seg = off;   off = pad256(off + (uint64_t)s.U * w->nseg * 8);
     w->sel = off;   off = pad256(off + s.T);
+    w->part = w->inv_norm = w->ranks_a = off;
+    if (s.m > 1) {
+        const uint64_t TA = s.T / s.m;
+        w->part = off;     off = pad256(off + s.T * 4);
+        w->inv_norm = off; off = pad256(off + TA * 4);
+        w->ranks_a = off;  off = pad256(off + ((TA + 63) / 64) * 4);
+    }
     w->total = off;
 }
 

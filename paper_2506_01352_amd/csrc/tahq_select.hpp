@@ -349,6 +349,32 @@ __global__ __launch_bounds__(256) void k_bitmap_pack(const uint8_t *__restrict__
     if ((threadIdx.x & 63) == 0 && (j >> 6) < ((uint64_t)T + 63) / 64) bitmap[j >> 6] = word;
 }
 
+// Allocation tiles of m > 1 quantization tiles (Sec. 3.2): the selection ran over allocation tiles and left
+// one byte per allocation tile in `sel_a` and, in `ranks_a`, the 4-bit allocation tiles before each group of
+// 64.  This kernel writes the stream's bit map and rank table over QUANTIZATION tiles: tile j takes the
+// width of allocation tile j / m, and the 4-bit quantization tiles before j are m times the 4-bit
+// allocation tiles before j / m, plus j % m if its own allocation tile has 4 bits.  One wavefront per
+// 64 quantization tiles.
+__global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict__ sel_a,
+                                                      const uint32_t *__restrict__ ranks_a, uint32_t T, uint32_t m,
+                                                      uint64_t *__restrict__ bitmap, uint32_t *__restrict__ ranks)
+{
+    const uint32_t j = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t j0 = j - lane;
+    if (j0 >= T) return;                               // whole wavefront past the end
+    const uint32_t ja0 = j0 / m, r0 = j0 % m;
+    const uint32_t base = ja0 & ~63u;
+    const bool before = base + lane < ja0 && sel_a[base + lane] != 0;
+    const uint32_t rank_a = ranks_a[ja0 >> 6] + (uint32_t)__popcll(__ballot(before));
+    const bool mine = j < T && sel_a[j < T ? j / m : 0] != 0;
+    const uint64_t word = __ballot(mine);
+    if (lane == 0) {
+        bitmap[j0 >> 6] = word;
+        ranks[j0 >> 6] = rank_a * m + (sel_a[ja0] != 0 ? r0 : 0u);
+    }
+}
+
 // Budget 3.0 or 4.0: every tile has the same width.
 __global__ __launch_bounds__(256) void k_bitmap_const(uint32_t T, int all4, uint64_t *__restrict__ bitmap,
                                                       uint32_t *__restrict__ ranks)

@@ -248,6 +248,67 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
     }
 }
 
+// ---------------------- entropy of allocation tiles wider than a quantization tile
+
+// Sec. 3.2 with A = m*G, m > 1: Eq. 1's norm and Eq. 2's sum run over the A channels of an allocation
+// tile.  Both are accumulated per quantization tile by the pairwise tree and then across the m tiles
+// from left to right, so the work splits into two streaming passes with a small reduction after each:
+//   WEIGHTED = false: part[j] = sum over tile j of |v|
+//   WEIGHTED = true:  part[j] = sum over tile j of p log(p + varsigma), p = |v| * inv_norm[j / m]
+// One workgroup per batch of tiles, one lane per tile.
+template <int G, bool BF16, bool WEIGHTED>
+__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
+void k_tile_partial(const void *__restrict__ in, const float *__restrict__ inv_norm, float *__restrict__ part,
+                    uint32_t T, uint32_t m, float eps_log)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    using B = Batch<G, ES>;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
+    const int tid = threadIdx.x;
+    const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
+    const uint32_t left = T - (uint32_t)j0;
+    const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
+    uint4 v[B::CHUNKS];
+    if (nvalid == (uint32_t)B::TILES) {
+        load_batch<G, ES, true, true>(in, j0, nvalid, v);
+        store_batch<G, ES, true>(v, nvalid, lds);
+    } else {
+        load_batch<G, ES, false>(in, j0, nvalid, v);
+        store_batch<G, ES, false>(v, nvalid, lds);
+    }
+    __syncthreads();
+    if ((uint32_t)tid >= nvalid) return;
+    const uint32_t j = (uint32_t)j0 + tid;
+    float a[G];
+    read_tile<G, BF16>(lds + tid * B::STRIDE, a);
+#pragma unroll
+    for (int k = 0; k < G; ++k) a[k] = __builtin_fabsf(a[k]);
+    if constexpr (WEIGHTED) {
+        const float invL = inv_norm[j / m];
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            const float p = a[k] * invL;
+            const float u = p + eps_log;
+            a[k] = p * log_contract(u);
+        }
+    }
+    part[j] = tree_sum<G>(a);
+}
+
+// Left-to-right sum of the m partial sums of every allocation tile.  FINAL = false: the reciprocal norm
+// 1 / (L1 + eps) of Eq. 1; FINAL = true: the entropy 0 - sum of Eq. 2.
+template <bool FINAL>
+__global__ __launch_bounds__(256) void k_alloc_reduce(const float *__restrict__ part, float *__restrict__ out,
+                                                      uint32_t n_alloc, uint32_t m, float eps_l1)
+{
+    const uint32_t ja = blockIdx.x * 256 + threadIdx.x;
+    if (ja >= n_alloc) return;
+    const float *p = part + (uint64_t)ja * m;
+    float acc = 0.0f;
+    for (uint32_t q = 0; q < m; ++q) acc = acc + p[q];
+    out[ja] = FINAL ? 0.0f - acc : 1.0f / (acc + eps_l1);
+}
+
 // ------------------------------------ K3: transform + quantize + pack
 
 // Payload unit: a tile's payload is b units of G/8 bytes (b = 3 or 4).

@@ -54,24 +54,30 @@ class Guarded:
         assert (r[:self.pad] == CANARY).all() and (r[self.pad + self.nbytes:] == CANARY).all(), "out-of-bounds write"
 
 
-def run_gpu(tahq, cfg, x, out_dtype):
-    """encode + decode on the GPU with guarded buffers; returns (entropy, packed, out) on the host."""
+def run_gpu(tahq, cfg, x, out_dtype, want_alloc_entropy=False):
+    """encode + decode on the GPU with guarded buffers; returns (entropy, packed, out) on the host, plus the
+    entropies of the allocation tiles if asked for."""
     d_in = to_device(x)
     n = x.size
     T = n // cfg.tile
     packed = Guarded(tahq.tahq_packed_size(cfg))
     ws = Guarded(tahq.tahq_workspace_size(cfg))
     ent = Guarded(4 * T)
+    ent_a = Guarded(4 * (n // (cfg.alloc_tile or cfg.tile)))
     esz = 4 if out_dtype == tahq.F32 else 2
     out = Guarded(esz * n)
     tahq.tahq_tile_entropy(cfg, d_in, ent.view)
+    tahq.tahq_alloc_tile_entropy(cfg, d_in, ent_a.view, ws.view)
+    ws.view.fill_(0x3C)         # the encoder must not rely on what the call above left behind
     tahq.tahq_encode(cfg, d_in, packed.view, ws.view)
     tahq.tahq_decode(cfg, packed.view, out.view, out_dtype)
     torch.cuda.synchronize()
-    for g in (packed, ws, ent, out):
+    for g in (packed, ws, ent, ent_a, out):
         g.check()
     H = ent.view.cpu().numpy().view(np.float32)
     o = out.view.cpu().numpy().view(np.float32 if out_dtype == tahq.F32 else np.uint16)
+    if want_alloc_entropy:
+        return H, packed.view.cpu().numpy(), o, ent_a.view.cpu().numpy().view(np.float32)
     return H, packed.view.cpu().numpy(), o
 
 
@@ -102,14 +108,17 @@ def check_case(tahq, x, B, S, Cc, G, dtype, budget, out_dtype=None, **kw):
     ocfg = o32.make_cfg(B, S, Cc, G, dtype, budget, **kw)
     out_dtype = dtype if out_dtype is None else out_dtype
     x = np.ascontiguousarray(x).reshape(B, S, Cc)
-    H, packed, out = run_gpu(tahq, cfg, x, out_dtype)
+    H, packed, out, HA = run_gpu(tahq, cfg, x, out_dtype, want_alloc_entropy=True)
     T = B * S * (Cc // G)
     wantH, _, _, _ = o32.tile_stats(ocfg, x)
     assert np.array_equal(H.view(np.uint32), wantH.view(np.uint32)), \
         f"entropy bits differ at tile {first_diff(H.view(np.uint32), wantH.view(np.uint32))}"
+    wantHA = o32.alloc_entropies(ocfg, x)
+    assert np.array_equal(HA.view(np.uint32), wantHA.view(np.uint32)), \
+        f"allocation-tile entropy bits differ at {first_diff(HA.view(np.uint32), wantHA.view(np.uint32))}"
     want = o32.encode(ocfg, x)
     n_units = 1 if kw.get("scope", 0) else B
-    compare_streams(packed, want, T, G, n_units, o32.k_per_unit(ocfg))
+    compare_streams(packed, want, T, G, n_units, o32.k_per_unit(ocfg) * o32.tiles_per_alloc(ocfg))
     want_out = o32.decode(ocfg, want, out_dtype)
     if out_dtype == tahq.F32:
         fin = np.isfinite(want_out)
@@ -176,6 +185,46 @@ def test_whole_tensor_ranking_scope(tahq):
     w, x = workloads.generate(2, batch=3, seq=20)
     _say("[case] scope=1")
     check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.4, scope=1)
+
+
+# Sec. 3.2 with allocation tiles of several quantization tiles, up to the whole token (A = C)
+WIDE = [
+    (1, dict(), 128), (1, dict(), 512),
+    (2, dict(batch=2, seq=40), 256), (2, dict(batch=2, seq=40), 2048), (2, dict(batch=3, seq=7), 128),
+    (3, dict(batch=2, seq=24), 512), (3, dict(batch=2, seq=24), 4096),
+    (4, dict(batch=2, seq=36), 512), (4, dict(batch=2, seq=36), 8192), (4, dict(batch=1, seq=130), 8192),
+    (5, dict(batch=3, seq=10), 160), (5, dict(batch=2, seq=33), 5120), (5, dict(batch=2, seq=33), 64),
+]
+
+
+@pytest.mark.parametrize("index,shape,A", WIDE)
+def test_allocation_tiles_of_several_quantization_tiles(tahq, index, shape, A):
+    w, x = workloads.generate(index, **shape)
+    for budget in (3.3, 3.0, 4.0):
+        _say(f"[case] {w.name} shape={w.batch}x{w.seq}x{w.hidden} A={A} budget={budget}")
+        check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, alloc_tile=A)
+    check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.6, alloc_tile=A, scope=1)
+
+
+@pytest.mark.parametrize("G", (32, 64, 128))
+def test_allocation_tiles_of_three_edge_tiles(tahq, G):
+    tiles = workloads.edge_tiles(G)
+    n = len(tiles) // 3 * 3
+    _say(f"[case] edge tiles G={G} A={3 * G}")
+    check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, 3.5, alloc_tile=3 * G)
+    check_case(tahq, workloads.f32_to_bf16_bits(tiles[:n]), n // 3, 1, 3 * G, G, tahq.BF16, 3.5, alloc_tile=3 * G)
+
+
+def test_allocation_tile_ties_and_many_small_units(tahq):
+    # all-zero tokens give allocation tiles of entropy exactly 0; 300 samples of 3 allocation tiles each
+    w, x = workloads.generate(5, batch=2, seq=64)
+    _say("[case] allocation-tile ties")
+    for budget in (3.1, 3.9):
+        check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, alloc_tile=640)
+    rng = np.random.default_rng(6)
+    y = rng.standard_normal((300, 3, 128)).astype(np.float32)
+    y[:, :, 17] *= 12.0
+    check_case(tahq, y, 300, 3, 128, 64, tahq.F32, 3.34, alloc_tile=128)
 
 
 def test_massive_entropy_ties_are_broken_by_index(tahq):
@@ -263,6 +312,27 @@ def test_full_size_configs_bit_exact(tahq, index):
     got = got.numpy() if w.dtype == tahq.F32 else got.view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(got.view(np.uint32 if w.dtype == tahq.F32 else np.uint16),
                           want_out.view(np.uint32 if w.dtype == tahq.F32 else np.uint16))
+
+
+def test_full_size_token_level_allocation_bit_exact(tahq):
+    # the headline tensor with A = C (Sec. 3.2's token-level special case) and with A = 2G
+    w, x = workloads.generate(4)
+    d_in = to_device(x)
+    T = w.elements // w.tile
+    for A in (w.hidden, 2 * w.tile):
+        _say(f"[case] full size {w.name} A={A}")
+        cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits, alloc_tile=A)
+        ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits, alloc_tile=A)
+        codec = tahq.Codec(cfg)
+        codec.encode(d_in)
+        codec.decode()
+        torch.cuda.synchronize()
+        want = o32.encode(ocfg, x)
+        compare_streams(codec.packed.cpu().numpy(), want, T, w.tile, w.batch, o32.k_per_unit(ocfg) * (A // w.tile))
+        want_out = o32.decode(ocfg, want, w.dtype)
+        got = codec.out.cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(got, want_out)
+        del codec
 
 
 # ------------------------------------- every (tile width, dtype) pair, several batches and a ragged tail
