@@ -63,10 +63,10 @@ MUTATIONS = [
 ]
 
 
-def _pin_calls():
-    """Every pin of test_oracle_pins as a list of zero-argument callables (parametrized ones expanded)."""
+def _pin_calls(module=pins):
+    """Every pin of a test module as a list of zero-argument callables (parametrized ones expanded)."""
     calls = []
-    for name, fn in sorted(vars(pins).items()):
+    for name, fn in sorted(vars(module).items()):
         if not name.startswith("test_") or not callable(fn):
             continue
         marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
@@ -89,9 +89,9 @@ def _pin_calls():
     return calls
 
 
-def _failing_pins(limit=1):
+def _failing_pins(limit=1, module=pins):
     failed = []
-    for name, call in _pin_calls():
+    for name, call in _pin_calls(module):
         try:
             call()
         except AssertionError:
@@ -107,25 +107,30 @@ def test_the_unmutated_oracle_passes_every_pin():
     assert _failing_pins(limit=1) == []
 
 
-@pytest.mark.parametrize("what,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
-def test_planted_mistake_is_caught_by_a_pin(what, old, new):
-    assert SRC.count(old) == 1, f"mutation anchor for '{what}' must match the oracle source exactly once"
-    saved = o32._lib
+def pins_failing_on_mutant(source, what, old, new, wrapper, lib_attr, module):
+    """Compile `source` with `old` replaced by `new`, point the ctypes wrapper at it, run the pins of `module`."""
+    assert source.count(old) == 1, f"mutation anchor for '{what}' must match the oracle source exactly once"
+    saved = wrapper._lib
     with tempfile.TemporaryDirectory() as tmp:
         src = os.path.join(tmp, "mutant.c")
         lib = os.path.join(tmp, "libmutant.so")
-        open(src, "w").write(SRC.replace(old, new))
+        open(src, "w").write(source.replace(old, new))
         flags = [f for f in build_oracle.CFLAGS if f != "-Werror"]
         subprocess.run(["gcc"] + flags + [src, "-o", lib, "-lm"], check=True)
         try:
-            o32._lib = None
-            orig = build_oracle.LIB
-            build_oracle.LIB = lib
+            wrapper._lib = None
+            orig = getattr(build_oracle, lib_attr)
+            setattr(build_oracle, lib_attr, lib)
             try:
-                o32.lib()
+                wrapper.lib()
             finally:
-                build_oracle.LIB = orig
-            failed = _failing_pins(limit=1)
+                setattr(build_oracle, lib_attr, orig)
+            failed = _failing_pins(limit=1, module=module)
         finally:
-            o32._lib = saved
-    assert failed, f"no pin notices: {what}"
+            wrapper._lib = saved
+    return failed
+
+
+@pytest.mark.parametrize("what,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught_by_a_pin(what, old, new):
+    assert pins_failing_on_mutant(SRC, what, old, new, o32, "LIB", pins), f"no pin notices: {what}"
