@@ -25,6 +25,13 @@ class tahq_config(C.Structure):
     ]
 
 
+class tahq_naive_config(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("batch", C.c_uint32), ("seq", C.c_uint32), ("hidden", C.c_uint32),
+        ("dtype", C.c_uint32), ("bits", C.c_uint32), ("scale", C.c_float),
+    ]
+
+
 _lib = None
 
 
@@ -67,6 +74,15 @@ def _load():
     L.tahq_status_string.argtypes = [C.c_int]
     L.tahq_version.restype = C.c_uint32
     L.tahq_version.argtypes = []
+    PN = C.POINTER(tahq_naive_config)
+    L.tahq_naive_config_default.restype = None
+    L.tahq_naive_config_default.argtypes = [PN]
+    L.tahq_naive_packed_size.restype = C.c_size_t
+    L.tahq_naive_packed_size.argtypes = [PN]
+    L.tahq_naive_encode.restype = C.c_int
+    L.tahq_naive_encode.argtypes = [PN, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tahq_naive_decode.restype = C.c_int
+    L.tahq_naive_decode.argtypes = [PN, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint32, C.c_void_p]
     _lib = L
     return L
 
@@ -179,6 +195,39 @@ def tahq_parse_header(header_bytes):
     if rc != 0:
         raise TahqError(rc, "tahq_parse_header")
     return cfg
+
+
+# ---- backward-pass fixed-point compressor (include/tahq_naive.h)
+
+def tahq_naive_config_default():
+    cfg = tahq_naive_config()
+    _load().tahq_naive_config_default(C.byref(cfg))
+    return cfg
+
+
+def make_naive_config(batch, seq, hidden, dtype, bits, scale=1.0):
+    cfg = tahq_naive_config_default()
+    cfg.batch, cfg.seq, cfg.hidden, cfg.dtype, cfg.bits, cfg.scale = batch, seq, hidden, dtype, bits, scale
+    return cfg
+
+
+def tahq_naive_packed_size(cfg):
+    return int(_load().tahq_naive_packed_size(C.byref(cfg)))
+
+
+def tahq_naive_encode(cfg, d_in, d_packed, stream=None, packed_capacity=None):
+    cap = _nbytes(d_packed) if packed_capacity is None else packed_capacity
+    rc = _load().tahq_naive_encode(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_packed), cap, _stream_handle(stream))
+    if rc != 0:
+        raise TahqError(rc, "tahq_naive_encode")
+
+
+def tahq_naive_decode(cfg, d_packed, d_out, out_dtype, stream=None, packed_bytes=None):
+    nbytes = _nbytes(d_packed) if packed_bytes is None else packed_bytes
+    rc = _load().tahq_naive_decode(C.byref(cfg), _dev_ptr(d_packed), nbytes, _dev_ptr(d_out), out_dtype,
+                                   _stream_handle(stream))
+    if rc != 0:
+        raise TahqError(rc, "tahq_naive_decode")
 
 
 class Codec:

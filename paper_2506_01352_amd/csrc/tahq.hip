@@ -15,6 +15,8 @@
 #include "tahq_common.hpp"
 #include "tahq_select.hpp"
 #include "tahq_stream_kernels.hpp"
+#include "tahq_naive_kernels.hpp"
+#include "tahq_naive.h"
 
 using namespace tahq;
 
@@ -120,6 +122,53 @@ bool launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, fl
                             fuse ? hist0 : (uint32_t *)nullptr, s.n, st);
     return fuse;
 }
+
+// ---- backward-pass fixed-point compressor
+
+struct NaiveShape {
+    uint64_t N;          // elements
+    uint32_t nchunks;    // chunks of 32 elements
+    uint32_t bits, dtype;
+    uint64_t total;      // stream bytes
+};
+
+tahq_status make_naive_shape(const tahq_naive_config *c, NaiveShape *s)
+{
+    if (!c) return TAHQ_ERR_NULL;
+    if (c->struct_size != sizeof(tahq_naive_config)) return TAHQ_ERR_INVALID_ARG;
+    if (c->batch == 0 || c->seq == 0 || c->hidden == 0 || c->hidden % kNaiveChunk != 0) return TAHQ_ERR_INVALID_ARG;
+    if (c->dtype > TAHQ_BF16 || c->bits < 2 || c->bits > 16) return TAHQ_ERR_INVALID_ARG;
+    if (!(c->scale > 0.0f) || c->scale > 3.4028234663852886e38f) return TAHQ_ERR_INVALID_ARG;
+    const uint64_t N = (uint64_t)c->batch * c->seq * c->hidden;
+    if (N > (1ull << 36)) return TAHQ_ERR_INVALID_ARG;
+    s->N = N;
+    s->nchunks = (uint32_t)(N / kNaiveChunk);
+    s->bits = c->bits;
+    s->dtype = c->dtype;
+    s->total = 64 + N * c->bits / 8;
+    return TAHQ_OK;
+}
+
+template <int BITS>
+void launch_naive_encode(bool bf16, const void *d_in, uint8_t *packed, const NaiveHeader &hdr, uint32_t nchunks,
+                         float scale, hipStream_t st)
+{
+    const dim3 grid((nchunks + kNaiveChunks - 1) / kNaiveChunks), block(kNaiveChunks);
+    if (bf16) hipLaunchKernelGGL((k_naive_encode<BITS, true>), grid, block, 0, st, d_in, packed, hdr, nchunks, scale);
+    else hipLaunchKernelGGL((k_naive_encode<BITS, false>), grid, block, 0, st, d_in, packed, hdr, nchunks, scale);
+}
+
+template <int BITS>
+void launch_naive_decode(bool out_bf16, const uint8_t *packed, void *d_out, uint32_t nchunks, float inv_scale,
+                         hipStream_t st)
+{
+    const dim3 grid((nchunks + kNaiveChunks - 1) / kNaiveChunks), block(kNaiveChunks);
+    if (out_bf16) hipLaunchKernelGGL((k_naive_decode<BITS, true>), grid, block, 0, st, packed, d_out, nchunks, inv_scale);
+    else hipLaunchKernelGGL((k_naive_decode<BITS, false>), grid, block, 0, st, packed, d_out, nchunks, inv_scale);
+}
+
+// Every supported code width, for the switch over the run-time width.
+#define TAHQ_NAIVE_WIDTHS(X) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
 
 }  // namespace
 
@@ -366,7 +415,71 @@ const char *tahq_status_string(tahq_status s)
     return "unknown status";
 }
 
-uint32_t tahq_version(void) { return (1u << 16) | 0u; }
+uint32_t tahq_version(void) { return (1u << 16) | 1u; }
+
+void tahq_naive_config_default(tahq_naive_config *cfg)
+{
+    if (!cfg) return;
+    memset(cfg, 0, sizeof *cfg);
+    cfg->struct_size = (uint32_t)sizeof *cfg;
+    cfg->dtype = TAHQ_BF16;
+    cfg->bits = 8;
+    cfg->scale = 1.0f;
+}
+
+size_t tahq_naive_packed_size(const tahq_naive_config *cfg)
+{
+    NaiveShape s;
+    if (make_naive_shape(cfg, &s) != TAHQ_OK) return 0;
+    return (size_t)s.total;
+}
+
+tahq_status tahq_naive_encode(const tahq_naive_config *cfg, const void *d_in, void *d_packed, size_t packed_capacity,
+                              tahq_stream stream)
+{
+    NaiveShape s;
+    tahq_status rc = make_naive_shape(cfg, &s);
+    if (rc != TAHQ_OK) return rc;
+    if (!d_in || !d_packed) return TAHQ_ERR_NULL;
+    if (packed_capacity < s.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
+    if (misaligned(d_in) || misaligned(d_packed)) return TAHQ_ERR_MISALIGNED;
+    NaiveHeader hdr;
+    memset(&hdr, 0, sizeof hdr);
+    hdr.w[0] = 0x4e484154u;   // "TAHN"
+    hdr.w[1] = 1;
+    hdr.w[2] = cfg->dtype; hdr.w[3] = cfg->batch; hdr.w[4] = cfg->seq; hdr.w[5] = cfg->hidden; hdr.w[6] = cfg->bits;
+    memcpy(&hdr.w[7], &cfg->scale, 4);
+    uint8_t *packed = static_cast<uint8_t *>(d_packed);
+    const bool bf16 = cfg->dtype == TAHQ_BF16;
+    switch (cfg->bits) {
+#define X(B) case B: launch_naive_encode<B>(bf16, d_in, packed, hdr, s.nchunks, cfg->scale, (hipStream_t)stream); break;
+        TAHQ_NAIVE_WIDTHS(X)
+#undef X
+    default: return TAHQ_ERR_INVALID_ARG;
+    }
+    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+}
+
+tahq_status tahq_naive_decode(const tahq_naive_config *cfg, const void *d_packed, size_t packed_bytes, void *d_out,
+                              uint32_t out_dtype, tahq_stream stream)
+{
+    NaiveShape s;
+    tahq_status rc = make_naive_shape(cfg, &s);
+    if (rc != TAHQ_OK) return rc;
+    if (out_dtype > TAHQ_BF16) return TAHQ_ERR_INVALID_ARG;
+    if (!d_packed || !d_out) return TAHQ_ERR_NULL;
+    if (packed_bytes < s.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
+    if (misaligned(d_packed) || misaligned(d_out)) return TAHQ_ERR_MISALIGNED;
+    const float inv_scale = 1.0f / cfg->scale;      // rounded once, on the host
+    const uint8_t *packed = static_cast<const uint8_t *>(d_packed);
+    switch (cfg->bits) {
+#define X(B) case B: launch_naive_decode<B>(out_dtype == TAHQ_BF16, packed, d_out, s.nchunks, inv_scale, (hipStream_t)stream); break;
+        TAHQ_NAIVE_WIDTHS(X)
+#undef X
+    default: return TAHQ_ERR_INVALID_ARG;
+    }
+    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+}
 
 }  // extern "C"
 

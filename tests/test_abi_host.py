@@ -16,10 +16,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    text = open(os.path.join(ROOT, "include", "tahq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(tahq_[a-z0-9_]+)\s*\(", text))
-    assert {"tahq_encode", "tahq_decode", "tahq_packed_size"} <= names
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tahq_[a-z0-9_]+)\s*\(", text))
+    assert {"tahq_encode", "tahq_decode", "tahq_packed_size", "tahq_naive_encode", "tahq_naive_decode"} <= names
     lib = C.CDLL(tahq.library_path())
     for n in sorted(names):
         assert hasattr(lib, n), n
@@ -131,3 +133,34 @@ def test_parse_header_round_trips_an_oracle_stream():
     broken = packed[:64].copy(); broken[0] = ord("X")
     with pytest.raises(tahq.TahqError):
         tahq.tahq_parse_header(broken.tobytes())
+
+
+def test_naive_codec_sizes_defaults_and_argument_errors():
+    from oracle import n32
+    d = tahq.tahq_naive_config_default()
+    assert d.struct_size == C.sizeof(tahq.tahq_naive_config) == 28 and (d.bits, d.scale, d.dtype) == (8, 1.0, 1)
+    for B, S, Cc, dt, bits, c in ((2, 3, 64, 0, 8, 1.0), (16, 2048, 5120, 1, 6, 16384.0), (1, 1, 32, 1, 2, 0.5),
+                                  (3, 5, 1600, 0, 16, 3.0), (1, 7, 96, 1, 7, 1e5), (8, 4096, 8192, 1, 10, 2.0 ** 20)):
+        cfg = tahq.make_naive_config(B, S, Cc, dt, bits, c)
+        assert tahq.tahq_naive_packed_size(cfg) == n32.packed_size(n32.make_cfg(B, S, Cc, dt, bits, c)) > 0
+    ok = dict(batch=2, seq=3, hidden=64, dtype=0, bits=8, scale=1.0)
+    for kw in (dict(batch=0), dict(seq=0), dict(hidden=0), dict(hidden=48), dict(dtype=2), dict(bits=1), dict(bits=17),
+               dict(scale=0.0), dict(scale=-1.0), dict(scale=float("nan")), dict(scale=float("inf"))):
+        bad = dict(ok); bad.update(kw)
+        assert tahq.tahq_naive_packed_size(tahq.make_naive_config(**bad)) == 0, kw
+    # never-dereferenced device addresses: all of these fail in host validation
+    lib = binding._load()
+    cfg = tahq.make_naive_config(**ok)
+    size = tahq.tahq_naive_packed_size(cfg)
+    A, B_ = 0x10000, 0x20000
+    assert lib.tahq_naive_encode(C.byref(cfg), None, B_, size, None) == 1
+    assert lib.tahq_naive_encode(C.byref(cfg), A, None, size, None) == 1
+    assert lib.tahq_naive_encode(C.byref(cfg), A, B_, size - 1, None) == 4
+    assert lib.tahq_naive_encode(C.byref(cfg), A + 8, B_, size, None) == 6
+    assert lib.tahq_naive_encode(None, A, B_, size, None) == 1
+    assert lib.tahq_naive_decode(C.byref(cfg), A, size, None, 0, None) == 1
+    assert lib.tahq_naive_decode(C.byref(cfg), A, size - 1, B_, 0, None) == 4
+    assert lib.tahq_naive_decode(C.byref(cfg), A, size, B_, 2, None) == 2
+    assert lib.tahq_naive_decode(C.byref(cfg), A, size, B_ + 4, 0, None) == 6
+    bad = tahq.make_naive_config(**dict(ok, bits=20))
+    assert lib.tahq_naive_encode(C.byref(bad), A, B_, 1 << 20, None) == 2
