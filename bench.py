@@ -6,6 +6,9 @@ roofline of the dominant kernel (measured live with events on the launch stream)
 oracle's throughput on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--alloc-tile A] [--no-cpu-baseline]
+
+`--codec naive [--bits 8] [--scale 16384]` measures the backward-pass fixed-point compressor instead
+(default workload: configuration 5, the gradient-like tensor) and prints the same kind of line.
 """
 import argparse
 import json
@@ -63,12 +66,95 @@ def cpu_baseline(index, w, alloc_tile):
     }
 
 
+def naive_main(args):
+    """tahq_naive_encode + tahq_naive_decode per step; both kernels are timed with events on every 4th step."""
+    import numpy as np
+    import torch
+    import workloads
+    import paper_2506_01352_amd as tahq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    tahq.binding._load()
+    index = args.config if args.config_given else 5
+    w, x = workloads.generate(index)
+    cfg = tahq.make_naive_config(w.batch, w.seq, w.hidden, w.dtype, args.bits, args.scale)
+    size = tahq.tahq_naive_packed_size(cfg)
+    if size == 0:
+        print("bench.py: invalid --bits / --scale for the fixed-point compressor", file=sys.stderr)
+        sys.exit(2)
+    d_in = torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+    packed = torch.empty(size, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty(w.elements, dtype=torch.bfloat16 if w.dtype else torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        tahq.tahq_naive_encode(cfg, d_in, packed, stream)
+        if ev:
+            ev[1].record(stream)
+        tahq.tahq_naive_decode(cfg, packed, out, w.dtype, stream)
+        if ev:
+            ev[2].record(stream)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    EVENT_EVERY = 4
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range((args.steps + EVENT_EVERY - 1) // EVENT_EVERY)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i // EVENT_EVERY] if i % EVENT_EVERY == 0 else None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    nbytes = w.elements * w.bytes_per_element
+    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    alg = nbytes + size                       # either kernel moves the tensor once and the stream once
+    dominant, dom_ms = ("k_naive_encode", enc_ms) if enc_ms >= dec_ms else ("k_naive_decode", dec_ms)
+    achieved = alg / (dom_ms * 1e-3) / 1e9
+    out_line = {
+        "metric": "fixed-point backward compressor: encode+decode GB/s of gradients on 1 MI355X",
+        "value": nbytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "codec": "naive", "shape": [w.batch, w.seq, w.hidden],
+                   "storage": "bf16" if w.dtype else "f32", "bits": args.bits, "scale": args.scale,
+                   "out_dtype": "same as input"},
+        "kernel_ms": {"k_naive_encode": enc_ms, "k_naive_decode": dec_ms},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg,
+                     "avg_launch_ms": dom_ms, "launches_timed": len(evs)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import n32
+        batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
+        ws, xs = workloads.generate(index, batch=batch)
+        ocfg = n32.make_cfg(ws.batch, ws.seq, ws.hidden, ws.dtype, args.bits, args.scale)
+        c0 = time.perf_counter()
+        p = n32.encode(ocfg, xs)
+        c1 = time.perf_counter()
+        n32.decode(ocfg, p, ws.dtype)
+        c2 = time.perf_counter()
+        out_line["cpu_baseline"] = {
+            "value": ws.elements * ws.bytes_per_element / (c2 - c0) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {batch} of {w.batch} samples of {w.name} ({ws.elements} elements): "
+                      f"encode {c1 - c0:.2f} s + decode {c2 - c1:.2f} s"}
+    print(json.dumps(out_line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (default: the metric's config)")
+    ap.add_argument("--config", type=int, default=None, help="workload index 1..5 (default 4: the metric's config)")
+    ap.add_argument("--codec", choices=("tahq", "naive"), default="tahq",
+                    help="tahq: the forward activation codec (the metric); naive: the backward fixed-point compressor")
+    ap.add_argument("--bits", type=int, default=8, help="--codec naive: code width, 2..16")
+    ap.add_argument("--scale", type=float, default=16384.0, help="--codec naive: the pre-scale c")
     ap.add_argument("--alloc-tile", type=int, default=0,
                     help="allocation tile A in channels, a multiple of the tile width (default 0: A = G, the "
                          "metric's configuration)")
@@ -80,6 +166,11 @@ def main():
     if args.gpus != 1:
         print("bench.py: this codec runs on one GPU; nothing here shards across GPUs (use --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    args.config_given = args.config is not None
+    if args.config is None:
+        args.config = 4
+    if args.codec == "naive":
+        return naive_main(args)
 
     import numpy as np
     import torch
