@@ -94,13 +94,19 @@ struct LaunchDecode {
 
 template <int G, bool BF16>
 struct LaunchAllocEntropy {
-    // Entropies of allocation tiles of m > 1 quantization tiles: two streaming passes over the tensor.
+    // Entropies of allocation tiles of m > 1 quantization tiles: one pass if a workgroup's batch holds whole
+    // allocation tiles, otherwise two streaming passes over the tensor.
     static void run(const void *d_in, float *d_H, float *part, float *inv_norm, uint32_t T, uint32_t m, float eps_l1,
                     float eps_log, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
         const uint32_t n_alloc = T / m;
+        if (B::TILES % m == 0) {
+            hipLaunchKernelGGL((k_alloc_entropy<G, BF16>), dim3(nb), dim3(B::TILES), 0, st, d_in, d_H, T, m, eps_l1,
+                               eps_log);
+            return;
+        }
         hipLaunchKernelGGL((k_tile_partial<G, BF16, false>), dim3(nb), dim3(B::TILES), 0, st, d_in,
                            (const float *)nullptr, part, T, m, eps_log);
         hipLaunchKernelGGL((k_alloc_reduce<false>), dim3(blocks_for(n_alloc)), dim3(256), 0, st, (const float *)part,

@@ -252,7 +252,8 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
 
 // Sec. 3.2 with A = m*G, m > 1: Eq. 1's norm and Eq. 2's sum run over the A channels of an allocation
 // tile.  Both are accumulated per quantization tile by the pairwise tree and then across the m tiles
-// from left to right, so the work splits into two streaming passes with a small reduction after each:
+// from left to right.  In general the work splits into two streaming passes with a small reduction after
+// each:
 //   WEIGHTED = false: part[j] = sum over tile j of |v|
 //   WEIGHTED = true:  part[j] = sum over tile j of p log(p + varsigma), p = |v| * inv_norm[j / m]
 // One workgroup per batch of tiles, one lane per tile.
@@ -293,6 +294,66 @@ void k_tile_partial(const void *__restrict__ in, const float *__restrict__ inv_n
         }
     }
     part[j] = tree_sum<G>(a);
+}
+
+// The same result in ONE pass over the tensor when a workgroup's batch holds whole allocation tiles
+// (m divides TILES): the per-tile sums meet in LDS, the first lane of every allocation tile adds its m
+// values from left to right, and the tile's magnitudes wait in registers meanwhile.
+template <int G, bool BF16>
+__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES), (G * (BF16 ? 2 : 4) <= 128 ? 4 : 1))
+void k_alloc_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, uint32_t m, float eps_l1,
+                     float eps_log)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    using B = Batch<G, ES>;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
+    __shared__ float part[B::TILES];
+    __shared__ float inv_norm[B::TILES];
+    const int tid = threadIdx.x;
+    const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
+    const uint32_t left = T - (uint32_t)j0;
+    const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;   // a multiple of m
+    uint4 v[B::CHUNKS];
+    if (nvalid == (uint32_t)B::TILES) {
+        load_batch<G, ES, true, true>(in, j0, nvalid, v);
+        store_batch<G, ES, true>(v, nvalid, lds);
+    } else {
+        load_batch<G, ES, false>(in, j0, nvalid, v);
+        store_batch<G, ES, false>(v, nvalid, lds);
+    }
+    __syncthreads();
+    const bool valid = (uint32_t)tid < nvalid;
+    const bool first = valid && (uint32_t)tid % m == 0;      // first quantization tile of its allocation tile
+    float a[G];
+    if (valid) {
+        read_tile<G, BF16>(lds + tid * B::STRIDE, a);
+#pragma unroll
+        for (int k = 0; k < G; ++k) a[k] = __builtin_fabsf(a[k]);
+        part[tid] = tree_sum<G>(a);
+    }
+    __syncthreads();
+    if (first) {
+        float acc = 0.0f;
+        for (uint32_t q = 0; q < m; ++q) acc = acc + part[tid + q];
+        inv_norm[(uint32_t)tid / m] = 1.0f / (acc + eps_l1);
+    }
+    __syncthreads();
+    if (valid) {
+        const float invL = inv_norm[(uint32_t)tid / m];
+#pragma unroll
+        for (int k = 0; k < G; ++k) {
+            const float p = a[k] * invL;
+            const float u = p + eps_log;
+            a[k] = p * log_contract(u);
+        }
+        part[tid] = tree_sum<G>(a);
+    }
+    __syncthreads();
+    if (first) {
+        float acc = 0.0f;
+        for (uint32_t q = 0; q < m; ++q) acc = acc + part[tid + q];
+        H[((uint32_t)j0 + tid) / m] = 0.0f - acc;
+    }
 }
 
 // Left-to-right sum of the m partial sums of every allocation tile.  FINAL = false: the reciprocal norm
