@@ -18,13 +18,14 @@ class Cfg(C.Structure):
         ("dtype", C.c_uint32), ("scope", C.c_uint32),
         ("budget_bits", C.c_float), ("tau", C.c_float),
         ("eps_l1", C.c_float), ("eps_log", C.c_float), ("eps_ratio", C.c_float),
-        ("alloc_tile", C.c_uint32),
+        ("alloc_tile", C.c_uint32), ("low_bits", C.c_uint32),
     ]
 
 
 def make_cfg(batch, seq, hidden, tile, dtype, budget_bits, tau=2.0, eps_l1=1e-8, eps_log=1e-8,
-             eps_ratio=1e-8, scope=0, alloc_tile=0):
-    return Cfg(batch, seq, hidden, tile, dtype, scope, budget_bits, tau, eps_l1, eps_log, eps_ratio, alloc_tile)
+             eps_ratio=1e-8, scope=0, alloc_tile=0, low_bits=0):
+    return Cfg(batch, seq, hidden, tile, dtype, scope, budget_bits, tau, eps_l1, eps_log, eps_ratio, alloc_tile,
+               low_bits)
 
 
 _lib = None
@@ -96,6 +97,10 @@ def n_tiles(cfg):
     return cfg.batch * cfg.seq * (cfg.hidden // cfg.tile)
 
 
+def low_bits(cfg):
+    return cfg.low_bits or 3
+
+
 def tiles_per_alloc(cfg):
     return cfg.alloc_tile // cfg.tile if cfg.alloc_tile else 1
 
@@ -131,7 +136,7 @@ def tile_stats(cfg, x):
 
 
 def allocate(cfg, H):
-    """H: one entropy per allocation tile; returns the width (3 or 4) of every quantization tile."""
+    """H: one entropy per allocation tile; returns the width (lo or lo+1) of every quantization tile."""
     H = np.ascontiguousarray(H, np.float32)
     assert H.size == n_tiles(cfg) // tiles_per_alloc(cfg)
     width = np.empty(n_tiles(cfg), np.uint8)

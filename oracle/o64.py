@@ -59,19 +59,19 @@ def inverse_transform(y, d):
     return np.asarray(y, np.float64) @ sylvester(G).T / np.sqrt(G) @ swap_matrix(G, d).T
 
 
-def k_per_unit(n, budget):
-    """Sec. 3.2: top-p% with p = budget - 3, rounded to the nearest tile count."""
-    return int(min(max(np.floor(float(budget) * n - 3.0 * n + 0.5), 0), n))
+def k_per_unit(n, budget, low=3):
+    """Sec. 3.2: top-p% with p = budget - low, rounded to the nearest tile count."""
+    return int(min(max(np.floor(float(budget) * n - float(low) * n + 0.5), 0), n))
 
 
-def allocate(H, n_units, k):
-    """Per ranking unit: the k highest entropies get 4 bits (ties: lower index), rest 3."""
+def allocate(H, n_units, k, low=3):
+    """Per ranking unit: the k highest entropies get low+1 bits (ties: lower index), the rest low."""
     H = np.asarray(H).reshape(n_units, -1)
     n = H.shape[1]
-    width = np.full(H.shape, 3, np.uint8)
+    width = np.full(H.shape, low, np.uint8)
     for u in range(n_units):
         order = np.lexsort((np.arange(n), -H[u].astype(np.float64)))
-        width[u, order[:k]] = 4
+        width[u, order[:k]] = low + 1
     return width.reshape(-1)
 
 
@@ -81,7 +81,7 @@ def _pad64(x):
     return (x + 63) // 64 * 64
 
 
-def section_offsets(T, G, n_units, k):
+def section_offsets(T, G, n_units, k, low=3):
     off = {}
     off["bitmap"] = 64
     off["ranks"] = off["bitmap"] + _pad64((T + 7) // 8)
@@ -89,14 +89,15 @@ def section_offsets(T, G, n_units, k):
     off["scale"] = off["pivot"] + _pad64(T)
     off["zero"] = off["scale"] + _pad64(2 * T)
     off["payload"] = off["zero"] + _pad64(2 * T)
-    off["total"] = off["payload"] + (G // 8) * (3 * T + n_units * k)
+    off["total"] = off["payload"] + (G // 8) * (low * T + n_units * k)
     return off
 
 
-def parse_stream(packed, T, G, n_units, k):
-    """Split the stream into its sections; codes come back as a [T,G] uint8 array."""
+def parse_stream(packed, T, G, n_units, k, low=3):
+    """Split the stream into its sections; codes come back as a [T,G] uint8 array.  k counts the wide
+    (low+1 bit) quantization tiles per ranking unit."""
     packed = np.asarray(packed, np.uint8)
-    off = section_offsets(T, G, n_units, k)
+    off = section_offsets(T, G, n_units, k, low)
     assert packed.size >= off["total"]
     hdr = packed[:64]
     bits = np.unpackbits(packed[off["bitmap"]:off["bitmap"] + (T + 7) // 8], bitorder="little")[:T]
@@ -104,11 +105,11 @@ def parse_stream(packed, T, G, n_units, k):
     pivot = packed[off["pivot"]:off["pivot"] + T]
     scale = packed[off["scale"]:off["scale"] + 2 * T].view("<f2")
     zero = packed[off["zero"]:off["zero"] + 2 * T].view("<f2")
-    width = np.where(bits == 1, 4, 3).astype(np.int64)
-    rank_of = np.concatenate([[0], np.cumsum(bits)[:-1]]).astype(np.int64)   # INT4 tiles before j
-    start = off["payload"] + (G // 8) * (3 * np.arange(T, dtype=np.int64) + rank_of)
+    width = np.where(bits == 1, low + 1, low).astype(np.int64)
+    rank_of = np.concatenate([[0], np.cumsum(bits)[:-1]]).astype(np.int64)   # wide tiles before j
+    start = off["payload"] + (G // 8) * (low * np.arange(T, dtype=np.int64) + rank_of)
     codes = np.zeros((T, G), np.uint8)
-    for b in (3, 4):
+    for b in (low, low + 1):
         sel = np.nonzero(width == b)[0]
         if sel.size == 0:
             continue
@@ -121,9 +122,9 @@ def parse_stream(packed, T, G, n_units, k):
                 width=width, rank_of=rank_of, codes=codes, offsets=off)
 
 
-def decode_stream(packed, T, G, n_units, k):
+def decode_stream(packed, T, G, n_units, k, low=3):
     """Alg. 1 step 5 in float64: q*s + z, then H^T and P_d for transformed tiles."""
-    s = parse_stream(packed, T, G, n_units, k)
+    s = parse_stream(packed, T, G, n_units, k, low)
     y = s["codes"].astype(np.float64) * s["scale"].astype(np.float64)[:, None] \
         + s["zero"].astype(np.float64)[:, None]
     out = y.copy()

@@ -38,12 +38,14 @@ typedef struct {
     uint32_t tile;        /* G = A (Sec. 3.2: default A = G) */
     uint32_t dtype;       /* 0 = fp32, 1 = bf16 (of the activation tensor) */
     uint32_t scope;       /* 0 = rank the tiles of every sample (Sec. 3.2); 1 = rank the whole tensor */
-    float budget_bits;    /* mean payload bits per element, in [3,4]; p% = budget-3 */
+    float budget_bits;    /* mean payload bits per element, in [lo, lo+1]; p% = budget-lo (lo = 3 by default) */
     float tau;            /* Eq. 3 threshold */
     float eps_l1;         /* epsilon of Eq. 1 */
     float eps_log;        /* varsigma of Eq. 2 */
     float eps_ratio;      /* varrho of Eq. 3 */
     uint32_t alloc_tile;  /* A: allocation-tile size (Sec. 3.2), a multiple of G dividing C; 0 means A = G */
+    uint32_t low_bits;    /* lo: the two widths are lo and lo+1.  3 (or 0) = INT3/INT4, the paper's setting;
+                             2 = the INT2/INT3 mix of the appendix on bit allocation */
 } tahq_oracle_cfg;
 
 enum { OR_OK = 0, OR_BAD = 1, OR_SMALL = 2 };
@@ -55,10 +57,15 @@ static int cfg_ok(const tahq_oracle_cfg *c)
     if (c->tile != 32 && c->tile != 64 && c->tile != 128) return 0;
     if (c->hidden % c->tile) return 0;
     if (c->dtype > 1 || c->scope > 1) return 0;
-    if (!(c->budget_bits >= 3.0f && c->budget_bits <= 4.0f)) return 0;
+    if (c->low_bits != 0 && c->low_bits != 2 && c->low_bits != 3) return 0;
+    float lo = c->low_bits ? (float)c->low_bits : 3.0f;
+    if (!(c->budget_bits >= lo && c->budget_bits <= lo + 1.0f)) return 0;
     if (c->alloc_tile != 0 && (c->alloc_tile % c->tile || c->hidden % c->alloc_tile)) return 0;
     return 1;
 }
+
+/* lo: the narrower of the two code widths. */
+static uint32_t low_bits(const tahq_oracle_cfg *c) { return c->low_bits ? c->low_bits : 3u; }
 
 /* m = A / G: quantization tiles per allocation tile (Sec. 3.2: A is aligned with the quantization tiles). */
 static uint32_t tiles_per_alloc(const tahq_oracle_cfg *c)
@@ -84,12 +91,12 @@ static uint64_t alloc_tiles_per_unit(const tahq_oracle_cfg *c)
 }
 static uint64_t n_units(const tahq_oracle_cfg *c) { return c->scope ? 1 : c->batch; }
 
-/* Sec. 3.2, top-p%: number of INT4 allocation tiles per ranking unit.  p = budget-3,
+/* Sec. 3.2, top-p%: number of wide (lo+1 bit, INT4 by default) allocation tiles per ranking unit.  p = budget-lo,
  * so the mean payload width is 3 + k/n.  Rounded to nearest, in double. */
 uint64_t tahq_oracle_k(const tahq_oracle_cfg *c)
 {
     double n = (double)alloc_tiles_per_unit(c);
-    double k = floor((double)c->budget_bits * n - 3.0 * n + 0.5);
+    double k = floor((double)c->budget_bits * n - (double)low_bits(c) * n + 0.5);
     if (k < 0) k = 0;
     if (k > n) k = n;
     return (uint64_t)k;
@@ -346,7 +353,7 @@ static void analyse_tile(const tahq_oracle_cfg *c, const float *v, float *y, til
  * coded range always covers [mn, mx]. */
 void tahq_oracle_quant_params(float mn, float mx, uint32_t b, uint16_t *s16, uint16_t *z16)
 {
-    float Lv = (b == 4) ? 15.0f : 7.0f;
+    float Lv = (float)((1u << b) - 1u);
     uint16_t z = tahq_oracle_fp16_down(mn);
     float mnf = tahq_oracle_fp16_widen(z);
     float s = (mx - mnf) / Lv;
@@ -358,7 +365,7 @@ void tahq_oracle_quant_params(float mn, float mx, uint32_t b, uint16_t *s16, uin
 
 uint32_t tahq_oracle_quant_code(float y, uint16_t s16, uint16_t z16, uint32_t b)
 {
-    float Lv = (b == 4) ? 15.0f : 7.0f;
+    float Lv = (float)((1u << b) - 1u);
     float sf = tahq_oracle_fp16_widen(s16);
     float mnf = tahq_oracle_fp16_widen(z16);
     float r = 1.0f / sf;
@@ -376,11 +383,11 @@ float tahq_oracle_dequant(uint32_t q, uint16_t s16, uint16_t z16)
 /* Little-endian; every section padded to 64 bytes, in this order:
  *   header   64 B
  *   bitmap   T bits: tile j -> byte j>>3, bit j&7; 1 = INT4
- *   ranks    uint32[ceil(T/64)]: INT4 tiles before each group of 64 tiles
+ *   ranks    uint32[ceil(T/64)]: wide (lo+1 bit) tiles before each group of 64 tiles
  *   pivot    uint8[T]
  *   scale    binary16[T]
  *   zero     binary16[T]
- *   payload  tile j at byte (G/8)*(3j + rank(j)), G*b/8 bytes, element k in
+ *   payload  tile j at byte (G/8)*(lo*j + rank(j)), G*b/8 bytes, element k in
  *            bits [b*k, b*k+b) of the tile's LSB-first bit string
  * The shape depends on the configuration only (Sec. 3.4: a fixed-shape buffer). */
 
@@ -398,7 +405,7 @@ static void make_layout(const tahq_oracle_cfg *c, layout *L)
     L->scale = L->pivot + pad64(T);
     L->zero = L->scale + pad64(2 * T);
     L->payload = L->zero + pad64(2 * T);
-    L->total = L->payload + (uint64_t)(c->tile / 8) * (3 * T + n_units(c) * k * tiles_per_alloc(c));
+    L->total = L->payload + (uint64_t)(c->tile / 8) * (low_bits(c) * T + n_units(c) * k * tiles_per_alloc(c));
 }
 
 uint64_t tahq_oracle_packed_size(const tahq_oracle_cfg *c)
@@ -437,6 +444,7 @@ static void write_header(const tahq_oracle_cfg *c, uint8_t *p)
     put_u32(p + 48, f32_bits(c->eps_log));
     put_u32(p + 52, f32_bits(c->eps_ratio));
     put_u32(p + 56, c->alloc_tile ? c->alloc_tile : c->tile);
+    put_u32(p + 60, low_bits(c));
 }
 
 /* --------------------------------------------------------- bit allocation */
@@ -459,14 +467,14 @@ int tahq_oracle_allocate(const tahq_oracle_cfg *c, const float *H, uint8_t *widt
 {
     if (!cfg_ok(c)) return OR_BAD;
     uint64_t n = alloc_tiles_per_unit(c), U = n_units(c), k = tahq_oracle_k(c);
-    uint32_t m = tiles_per_alloc(c);
+    uint32_t m = tiles_per_alloc(c), lo = low_bits(c);
     rank_item *it = (rank_item *)malloc((size_t)n * sizeof *it);
     if (!it) return OR_BAD;
     for (uint64_t u = 0; u < U; ++u) {
         for (uint64_t j = 0; j < n; ++j) { it[j].H = H[u * n + j]; it[j].j = j; }
         qsort(it, (size_t)n, sizeof *it, by_entropy_desc_then_index);
         for (uint64_t r = 0; r < n; ++r)
-            for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (r < k) ? 4 : 3;
+            for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (uint8_t)((r < k) ? lo + 1 : lo);
     }
     free(it);
     return OR_OK;
@@ -515,7 +523,7 @@ int tahq_oracle_encode(const tahq_oracle_cfg *c, const void *in, uint8_t *packed
     layout L; make_layout(c, &L);
     if (cap < L.total) return OR_SMALL;
     uint64_t T = n_tiles(c);
-    uint32_t G = c->tile;
+    uint32_t G = c->tile, lo = low_bits(c);
 
     float *H = (float *)malloc((size_t)T * sizeof(float));
     uint8_t *width = (uint8_t *)malloc((size_t)T);
@@ -532,11 +540,11 @@ int tahq_oracle_encode(const tahq_oracle_cfg *c, const void *in, uint8_t *packed
     write_header(c, packed);
 
     /* pass 2: transform, quantize, pack */
-    uint64_t rank = 0;   /* INT4 tiles before tile j */
+    uint64_t rank = 0;   /* wide (lo+1 bit) tiles before tile j */
     for (uint64_t j = 0; j < T; ++j) {
         if ((j & 63u) == 0) put_u32(packed + L.ranks + 4 * (j >> 6), (uint32_t)rank);
         uint32_t b = width[j];
-        if (b == 4) packed[L.bitmap + (j >> 3)] |= (uint8_t)(1u << (j & 7u));
+        if (b == lo + 1) packed[L.bitmap + (j >> 3)] |= (uint8_t)(1u << (j & 7u));
 
         load_tile(c, in, j, v);
         analyse_tile(c, v, y, &r);
@@ -547,7 +555,7 @@ int tahq_oracle_encode(const tahq_oracle_cfg *c, const void *in, uint8_t *packed
         put_u16(packed + L.scale + 2 * j, s16);
         put_u16(packed + L.zero + 2 * j, z16);
 
-        uint8_t *dst = packed + L.payload + (uint64_t)(G / 8) * (3 * j + rank);
+        uint8_t *dst = packed + L.payload + (uint64_t)(G / 8) * (lo * j + rank);
         for (uint32_t k = 0; k < G; ++k) {
             uint32_t q = tahq_oracle_quant_code(y[k], s16, z16, b);
             uint32_t bit = b * k;
@@ -555,7 +563,7 @@ int tahq_oracle_encode(const tahq_oracle_cfg *c, const void *in, uint8_t *packed
             dst[bit >> 3] |= (uint8_t)(q << (bit & 7u));
             if ((bit & 7u) + b > 8) dst[(bit >> 3) + 1] |= (uint8_t)(q >> (8 - (bit & 7u)));
         }
-        if (b == 4) ++rank;
+        if (b == lo + 1) ++rank;
     }
     free(H); free(width);
     return OR_OK;
@@ -572,10 +580,10 @@ int tahq_oracle_decode(const tahq_oracle_cfg *c, const uint8_t *packed, uint64_t
     layout L; make_layout(c, &L);
     if (bytes < L.total) return OR_SMALL;
     uint64_t T = n_tiles(c);
-    uint32_t G = c->tile;
+    uint32_t G = c->tile, lo = low_bits(c);
     float y[128];
     for (uint64_t j = 0; j < T; ++j) {
-        uint32_t b = ((packed[L.bitmap + (j >> 3)] >> (j & 7u)) & 1u) ? 4 : 3;
+        uint32_t b = ((packed[L.bitmap + (j >> 3)] >> (j & 7u)) & 1u) ? lo + 1 : lo;
         /* rank(j): table entry of the group plus set bits below j inside it */
         uint64_t rank = get_u32(packed + L.ranks + 4 * (j >> 6));
         for (uint64_t i = j & ~(uint64_t)63u; i < j; ++i)
@@ -583,7 +591,7 @@ int tahq_oracle_decode(const tahq_oracle_cfg *c, const uint8_t *packed, uint64_t
         uint16_t s16 = get_u16(packed + L.scale + 2 * j);
         uint16_t z16 = get_u16(packed + L.zero + 2 * j);
         uint8_t pv = packed[L.pivot + j];
-        const uint8_t *src = packed + L.payload + (uint64_t)(G / 8) * (3 * j + rank);
+        const uint8_t *src = packed + L.payload + (uint64_t)(G / 8) * (lo * j + rank);
         for (uint32_t k = 0; k < G; ++k) {
             uint32_t bit = b * k;
             uint32_t w = src[bit >> 3];

@@ -23,8 +23,8 @@ MUTATIONS = [
     ("allocation tile norm keeps only its last quantization tile", "L1 = L1 + tree_sum(w, G);", "L1 = tree_sum(w, G);"),
     ("k counted over quantization tiles", "double n = (double)alloc_tiles_per_unit(c);", "double n = (double)tiles_per_unit(c);"),
     ("width written to the first quantization tile of an allocation tile only",
-     "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (r < k) ? 4 : 3;",
-     "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (r < k && q == 0) ? 4 : 3;"),
+     "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (uint8_t)((r < k) ? lo + 1 : lo);",
+     "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (uint8_t)((r < k && q == 0) ? lo + 1 : lo);"),
     ("log polynomial coefficient off by 2x", "0x1.c4859ep+2f", "0x1.c4859ep+1f"),
     ("butterfly difference with swapped operands", "v[j + h] = x - y;", "v[j + h] = y - x;"),
     ("wrong 1/sqrt(G) for G = 64", "(G == 64 ? 0.125f :", "(G == 64 ? 0.25f :"),
@@ -43,9 +43,11 @@ MUTATIONS = [
      "return (a->j < b->j) - (a->j > b->j);"),
     ("allocation picks the lowest entropies", "if (a->H > b->H) return -1;\n    if (a->H < b->H) return 1;",
      "if (a->H > b->H) return 1;\n    if (a->H < b->H) return -1;"),
-    ("k truncated instead of rounded", "- 3.0 * n + 0.5);", "- 3.0 * n);"),
+    ("k truncated instead of rounded", "* n + 0.5);", "* n);"),
     ("quantizer rounds half up", "rintf(t)", "floorf(t + 0.5f)"),
-    ("quantizer uses 2^b steps", "float Lv = (b == 4) ? 15.0f : 7.0f;\n    uint16_t z", "float Lv = (b == 4) ? 16.0f : 8.0f;\n    uint16_t z"),
+    ("quantizer uses 2^b steps", "float Lv = (float)((1u << b) - 1u);\n    uint16_t z", "float Lv = (float)(1u << b);\n    uint16_t z"),
+    ("k counted from three bits whatever the low width", "- (double)low_bits(c) * n + 0.5);", "- 3.0 * n + 0.5);"),
+    # (planted mistakes must keep the mutant inside its buffers: it runs in this process)
     ("zero-point rounded to nearest instead of down",
      "if (tahq_oracle_fp16_widen(h) > xc) h = fp16_prev(h);", ""),
     ("scale rounded to nearest instead of up",
@@ -53,7 +55,7 @@ MUTATIONS = [
     ("payload elements in reverse order", "uint32_t bit = b * k;\n            /* a code spans", "uint32_t bit = b * (G - 1 - k);\n            /* a code spans"),
     ("rank table off by one", "put_u32(packed + L.ranks + 4 * (j >> 6), (uint32_t)rank);",
      "put_u32(packed + L.ranks + 4 * (j >> 6), (uint32_t)rank + 1);"),
-    ("bit map marks three-bit tiles", "if (b == 4) packed[L.bitmap + (j >> 3)] |=", "if (b == 3) packed[L.bitmap + (j >> 3)] |="),
+    ("bit map marks three-bit tiles", "if (b == lo + 1) packed[L.bitmap + (j >> 3)] |=", "if (b == lo) packed[L.bitmap + (j >> 3)] |="),
     ("de-quantization without the zero-point", "return fmaf((float)q, tahq_oracle_fp16_widen(s16), tahq_oracle_fp16_widen(z16));",
      "(void)z16; return (float)q * tahq_oracle_fp16_widen(s16);"),
     ("bf16 narrowing truncates", "u += 0x7fffu + lsb;", "(void)lsb;"),

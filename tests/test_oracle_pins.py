@@ -253,7 +253,7 @@ def test_bf16_rne_against_torch():
 
 # ---------------------------------------------------------- quantizer
 
-@pytest.mark.parametrize("b", (3, 4))
+@pytest.mark.parametrize("b", (2, 3, 4))
 def test_quantizer_half_step_bound_and_coverage(b):
     rng = np.random.default_rng(10 + b)
     L = (1 << b) - 1
@@ -276,6 +276,7 @@ def test_quantizer_rounds_half_to_even_and_clamps():
     assert [o32.quant_code(v, s16, z16, 4) for v in (0.5, 1.5, 2.5, 3.5, 14.5, 15.4, 99.0, -3.0)] == \
         [0, 2, 2, 4, 14, 15, 15, 0]
     assert [o32.quant_code(v, s16, z16, 3) for v in (6.5, 7.49, 7.5, 8.0)] == [6, 7, 7, 7]
+    assert [o32.quant_code(v, s16, z16, 2) for v in (0.5, 1.5, 2.5, 2.51, 3.5, 9.0, -1.0)] == [0, 2, 2, 3, 3, 3, 0]
     assert o32.quant_code(float("nan"), s16, z16, 4) == 0
 
 
@@ -292,7 +293,7 @@ def test_quantizer_agrees_with_textbook_minmax_when_metadata_is_exact():
     # Values on a binary grid with float16-exact min and scale: codes must equal the float64
     # textbook min-max group quantizer, except exactly-half ties which both round to even.
     rng = np.random.default_rng(21)
-    for b in (3, 4):
+    for b in (2, 3, 4):
         L = (1 << b) - 1
         for _ in range(50):
             q_true = rng.integers(0, L + 1, size=64)
@@ -457,6 +458,79 @@ def test_allocation_tile_must_align_with_quantization_tiles_and_divide_the_hidde
     assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=256)) == 0    # does not divide C
     assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=32)) == 0     # below G
     assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=192)) > 0
+
+
+# ------------------------------------------- the INT2/INT3 mix (lo = 2)
+
+def test_low_bits_changes_the_two_widths_the_budget_range_and_the_count():
+    # appendix on bit allocation: 80% INT2 + 20% INT3 is budget 2.2 with widths {2, 3}
+    cfg = o32.make_cfg(2, 10, 512, 64, o32.F32, 2.2, low_bits=2)
+    n = 10 * 8
+    assert o32.k_per_unit(cfg) == 16 == o64.k_per_unit(n, 2.2, low=2)
+    H = np.arange(2 * n, dtype=np.float32)
+    width = o32.allocate(cfg, H)
+    assert set(np.unique(width)) == {2, 3} and (width == 3).sum() == 32
+    assert np.array_equal(width, o64.allocate(H, 2, 16, low=2))
+    assert math.isclose(width.mean(), 2.2)
+    # the budget must lie in [lo, lo + 1]
+    assert o32.packed_size(o32.make_cfg(2, 10, 512, 64, o32.F32, 3.2, low_bits=2)) == 0
+    assert o32.packed_size(o32.make_cfg(2, 10, 512, 64, o32.F32, 1.9, low_bits=2)) == 0
+    assert o32.packed_size(o32.make_cfg(2, 10, 512, 64, o32.F32, 2.2, low_bits=3)) == 0
+    assert o32.packed_size(o32.make_cfg(2, 10, 512, 64, o32.F32, 2.2, low_bits=4)) == 0
+    assert o32.packed_size(o32.make_cfg(2, 10, 512, 64, o32.F32, 3.0, low_bits=2)) > 0
+    # lo = 3 written out is the default
+    w, x = workloads.generate(1, batch=1, seq=8)
+    a = o32.encode(o32.make_cfg(1, 8, w.hidden, w.tile, w.dtype, 3.5), x)
+    b = o32.encode(o32.make_cfg(1, 8, w.hidden, w.tile, w.dtype, 3.5, low_bits=3), x)
+    assert np.array_equal(a, b) and a[:64].view("<u4")[15] == 3
+
+
+@pytest.mark.parametrize("index,shape,budget", [(1, dict(batch=1, seq=16), 2.2), (2, dict(batch=2, seq=24), 2.5),
+                                                (3, dict(batch=2, seq=8), 2.0), (4, dict(batch=2, seq=40), 2.2),
+                                                (5, dict(batch=2, seq=16), 3.0), (4, dict(batch=1, seq=12), 2.75)])
+def test_int2_int3_stream_parses_and_decodes_independently_in_float64(index, shape, budget):
+    w, x = workloads.generate(index, **shape)
+    cfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, low_bits=2)
+    packed = o32.encode(cfg, x)
+    T, G = o32.n_tiles(cfg), w.tile
+    k = o32.k_per_unit(cfg)
+    assert packed.size == o32.packed_size(cfg) == o64.section_offsets(T, G, w.batch, k, low=2)["total"]
+    out64, s = o64.decode_stream(packed, T, G, w.batch, k, low=2)
+    hdr = s["header"].view("<u4")
+    assert list(hdr[1:9]) == [1, w.dtype, w.batch, w.seq, w.hidden, G, 0, k] and hdr[15] == 2
+    H, pivot, mn, mx = o32.tile_stats(cfg, x)
+    assert np.array_equal(s["bits"].reshape(w.batch, -1).sum(axis=1), np.full(w.batch, k))
+    assert np.array_equal(s["width"], o64.allocate(H, w.batch, k, low=2))
+    assert np.array_equal(s["ranks"], s["rank_of"][::64])
+    assert np.array_equal(s["pivot"], pivot)
+    sf = s["scale"].astype(np.float64); zf = s["zero"].astype(np.float64)
+    L = (1 << s["width"]) - 1
+    assert set(np.unique(L)) <= {3, 7}
+    assert np.all(zf <= mn) and np.all(zf + L * sf >= mx) and np.all(s["codes"] <= L[:, None])
+    out32 = o32.decode(cfg, packed, o32.F32).reshape(T, G).astype(np.float64)
+    scale = np.maximum(np.abs(out64).max(axis=1, keepdims=True), 1e-30)
+    assert np.max(np.abs(out32 - out64) / scale) < 1e-5
+    xf = (x if w.dtype == workloads.F32 else workloads.bf16_bits_to_f32(x)).reshape(T, G).astype(np.float64)
+    err = np.linalg.norm(out64 - xf, axis=1)
+    assert np.all(err <= sf / 2 * math.sqrt(G) * (1 + 1e-3) + 1e-6 * np.abs(xf).max(axis=1))
+    # fewer levels, larger steps: the INT2/INT3 stream is coarser than INT3/INT4 at the same fraction of wide tiles
+    cfg34 = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, budget + 1.0)
+    out34 = o32.decode(cfg34, o32.encode(cfg34, x), o32.F32).astype(np.float64)
+    assert np.linalg.norm(out64.reshape(-1) - xf.reshape(-1)) > 1.5 * np.linalg.norm(out34 - xf.reshape(-1))
+
+
+def test_two_bit_codes_fill_a_quarter_byte_each_in_element_order():
+    # one tile, values exactly on the four levels: codes 0..3 repeated, element i at bits [2i, 2i+2)
+    G = 32
+    x = np.tile(np.array([0.0, 1.0, 2.0, 3.0], np.float32), G // 4).reshape(1, 1, G)
+    cfg = o32.make_cfg(1, 1, G, G, o32.F32, 2.0, tau=float("inf"), low_bits=2)
+    packed = o32.encode(cfg, x)
+    s = o64.parse_stream(packed, 1, G, 1, 0, low=2)
+    assert float(s["scale"][0]) == 1.0 and float(s["zero"][0]) == 0.0
+    assert np.array_equal(s["codes"][0], np.tile([0, 1, 2, 3], G // 4))
+    pay = packed[s["offsets"]["payload"]:]
+    assert pay.size == G * 2 // 8 and (pay == 0b11100100).all()
+    assert np.array_equal(o32.decode(cfg, packed).reshape(x.shape), x)
 
 
 # -------------------------------------------------------------- format
