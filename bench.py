@@ -46,13 +46,13 @@ def algorithmic_bytes(w, packed_size, T, select):
     }
 
 
-def cpu_baseline(index, w, alloc_tile):
+def cpu_baseline(index, w, alloc_tile, low_bits, budget):
     """The oracle as it stands, single thread, on a bounded sample of the same workload."""
     import workloads
     from oracle import o32
     batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
     ws, x = workloads.generate(index, batch=batch)
-    ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, ws.tile, ws.dtype, ws.budget_bits, alloc_tile=alloc_tile)
+    ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, ws.tile, ws.dtype, budget, alloc_tile=alloc_tile, low_bits=low_bits)
     t0 = time.perf_counter()
     packed = o32.encode(ocfg, x)
     t1 = time.perf_counter()
@@ -158,6 +158,11 @@ def main():
     ap.add_argument("--alloc-tile", type=int, default=0,
                     help="allocation tile A in channels, a multiple of the tile width (default 0: A = G, the "
                          "metric's configuration)")
+    ap.add_argument("--low-bits", type=int, default=0, choices=(0, 2, 3),
+                    help="the two code widths are lo and lo+1 (default 0: 3, the metric's INT3/INT4)")
+    ap.add_argument("--budget", type=float, default=None,
+                    help="mean payload bits per element (default: the workload's own; with --low-bits 2 the default "
+                         "is the workload's minus one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of the input tensor (known size), so that a rocprofv3 --pmc "
@@ -182,9 +187,12 @@ def main():
     tahq.binding._load()
 
     w, x = workloads.generate(args.config)
-    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits, alloc_tile=args.alloc_tile)
+    budget = args.budget if args.budget is not None else w.budget_bits - (1.0 if args.low_bits == 2 else 0.0)
+    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, alloc_tile=args.alloc_tile,
+                           low_bits=args.low_bits)
     if tahq.tahq_packed_size(cfg) == 0:
-        print("bench.py: --alloc-tile must be a multiple of the tile width that divides the hidden size", file=sys.stderr)
+        print("bench.py: --alloc-tile must be a multiple of the tile width that divides the hidden size, and "
+              "--budget must lie in [lo, lo+1]", file=sys.stderr)
         sys.exit(2)
     wide = args.alloc_tile not in (0, w.tile)
     d_in = torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
@@ -273,7 +281,9 @@ def main():
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     dom_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
-    traffic = TRAFFIC_BYTES.get((w.name, dominant))
+    # the stored counter readings belong to the metric's own configuration
+    stock = not wide and args.low_bits in (0, 3) and budget == w.budget_bits
+    traffic = TRAFFIC_BYTES.get((w.name, dominant)) if stock else None
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -286,14 +296,15 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "shape": [w.batch, w.seq, w.hidden], "storage": "bf16" if w.dtype else "f32",
-                   "tile": w.tile, "alloc_tile": args.alloc_tile or w.tile, "budget_bits": w.budget_bits,
+                   "tile": w.tile, "alloc_tile": args.alloc_tile or w.tile, "budget_bits": budget,
+                   "widths": [args.low_bits or 3, (args.low_bits or 3) + 1],
                    "out_dtype": "same as input"},
         "pct_hbm_peak_of_activation_rate": 100.0 * value / HBM_PEAK_GBS,
         "warmup_phase_ms": warm_ms,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, w, args.alloc_tile)
+        out["cpu_baseline"] = cpu_baseline(args.config, w, args.alloc_tile, args.low_bits, budget)
     print(json.dumps(out))
 
 

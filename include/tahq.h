@@ -36,13 +36,13 @@
  * Stream layout (little-endian; every section padded to 64 bytes), T = number
  * of tiles = batch*seq*hidden/tile, k = 4-bit allocation tiles per ranking unit:
  *   header   64 B   "TAHQ", version, dtype, batch, seq, hidden, tile, scope, k,
- *                   budget, tau, eps_l1, eps_log, eps_ratio, A (32-bit words), zero
- *   bitmap   T bits         tile j -> byte j>>3, bit j&7; 1 = 4-bit tile
- *   ranks    uint32[ceil(T/64)]   4-bit tiles before each group of 64 tiles
+ *                   budget, tau, eps_l1, eps_log, eps_ratio, A, lo (32-bit words)
+ *   bitmap   T bits         tile j -> byte j>>3, bit j&7; 1 = wide tile (lo+1 bits; 4 by default)
+ *   ranks    uint32[ceil(T/64)]   wide tiles before each group of 64 tiles
  *   pivot    uint8[T]       bit 7 = tile was transformed, bits 0..6 = pivot index d
  *   scale    binary16[T]    quantization step (rounded up)
  *   zero     binary16[T]    zero-point = tile minimum (rounded down)
- *   payload  tile j at byte (tile/8)*(3j + rank(j)), tile*b/8 bytes; element i
+ *   payload  tile j at byte (tile/8)*(lo*j + rank(j)), tile*b/8 bytes; element i
  *            occupies bits [b*i, b*i+b) of the tile's LSB-first bit string
  */
 #ifndef TAHQ_H
@@ -74,21 +74,25 @@ typedef enum {
 typedef enum { TAHQ_F32 = 0, TAHQ_BF16 = 1 } tahq_dtype;
 
 typedef struct {
-    uint32_t struct_size;   /* = sizeof(tahq_config); set by tahq_config_default.  48 (a caller built
-                               before alloc_tile existed) is accepted and means alloc_tile = 0      */
+    uint32_t struct_size;   /* = sizeof(tahq_config); set by tahq_config_default.  48 and 52 (callers built
+                               before alloc_tile / low_bits existed) are accepted; the missing
+                               fields then count as 0                                               */
     uint32_t batch;         /* B                                                                  */
     uint32_t seq;           /* S                                                                  */
     uint32_t hidden;        /* C; tensor is contiguous row-major [B, S, C]                        */
     uint32_t tile;          /* G, the quantization tile: 32, 64 or 128                            */
     uint32_t dtype;         /* tahq_dtype of the activation tensor                                */
     uint32_t scope;         /* 0 = rank the tiles of every sample (the paper); 1 = rank the whole tensor */
-    float budget_bits;      /* mean payload bits per element, in [3.0, 4.0]                       */
+    float budget_bits;      /* mean payload bits per element, in [lo, lo+1] = [3.0, 4.0] by default */
     float tau;              /* outlier threshold of Eq. 3; default 2.0; +inf = never transform    */
     float eps_l1;           /* epsilon of Eq. 1;   default 1e-8                                   */
     float eps_log;          /* varsigma of Eq. 2;  default 1e-8                                   */
     float eps_ratio;        /* varrho of Eq. 3;    default 1e-8                                   */
     uint32_t alloc_tile;    /* A, the allocation tile of Sec. 3.2: a multiple of G that divides C;
                                0 = G (the paper's default); A = C is token-level allocation        */
+    uint32_t low_bits;      /* lo: the two code widths are lo and lo+1 bits and budget_bits lies in
+                               [lo, lo+1].  3 (or 0) = INT3/INT4, the paper's setting; 2 = the
+                               INT2/INT3 mix of the appendix on bit allocation                     */
 } tahq_config;
 
 /* Fill *cfg with the defaults (tile 64, budget 3.8, tau 2.0, eps 1e-8, scope 0,

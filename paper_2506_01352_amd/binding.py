@@ -21,7 +21,7 @@ class tahq_config(C.Structure):
         ("tile", C.c_uint32), ("dtype", C.c_uint32), ("scope", C.c_uint32),
         ("budget_bits", C.c_float), ("tau", C.c_float),
         ("eps_l1", C.c_float), ("eps_log", C.c_float), ("eps_ratio", C.c_float),
-        ("alloc_tile", C.c_uint32),
+        ("alloc_tile", C.c_uint32), ("low_bits", C.c_uint32),
     ]
 
 
@@ -94,9 +94,10 @@ def tahq_config_default():
 
 
 def make_config(batch, seq, hidden, tile, dtype, budget_bits, tau=2.0, eps_l1=1e-8, eps_log=1e-8,
-                eps_ratio=1e-8, scope=0, alloc_tile=0):
+                eps_ratio=1e-8, scope=0, alloc_tile=0, low_bits=0):
     cfg = tahq_config_default()
     cfg.alloc_tile = alloc_tile
+    cfg.low_bits = low_bits
     cfg.batch, cfg.seq, cfg.hidden, cfg.tile = batch, seq, hidden, tile
     cfg.dtype, cfg.scope = dtype, scope
     cfg.budget_bits, cfg.tau = budget_bits, tau

@@ -69,26 +69,41 @@ struct CanFuse {
     static void run(uint64_t n_per_unit, bool *out) { *out = LaunchEntropy<G, BF16>::can_fuse_histogram(n_per_unit); }
 };
 
+// `low`: the narrower of the two code widths, 3 (INT3/INT4) or 2 (INT2/INT3).
 template <int G, bool BF16>
 struct LaunchQuantPack {
-    static void run(const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio, hipStream_t st)
+    template <int LOW>
+    static void go(const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
-        hipLaunchKernelGGL((k_quant_pack<G, BF16>), dim3(nb), dim3(B::TILES), 0, st, d_in, packed, lay, T, tau,
+        hipLaunchKernelGGL((k_quant_pack<G, BF16, LOW>), dim3(nb), dim3(B::TILES), 0, st, d_in, packed, lay, T, tau,
                            eps_ratio);
+    }
+    static void run(uint32_t low, const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio,
+                    hipStream_t st)
+    {
+        if (low == 3u) go<3>(d_in, packed, lay, T, tau, eps_ratio, st);
+        else go<2>(d_in, packed, lay, T, tau, eps_ratio, st);
     }
 };
 
 template <int G, bool BF16>
 struct LaunchDecode {
-    static void run(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total4, hipStream_t st)
+    template <int LOW>
+    static void go(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total_wide, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
-        static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_decode<G, BF16>), B::TILES);
-        hipLaunchKernelGGL((k_decode<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, packed, d_out, lay, T,
-                           total4);
+        static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_decode<G, BF16, LOW>), B::TILES);
+        hipLaunchKernelGGL((k_decode<G, BF16, LOW>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, packed, d_out, lay,
+                           T, total_wide);
+    }
+    static void run(uint32_t low, const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total_wide,
+                    hipStream_t st)
+    {
+        if (low == 3u) go<3>(packed, d_out, lay, T, total_wide, st);
+        else go<2>(packed, d_out, lay, T, total_wide, st);
     }
 };
 
@@ -290,6 +305,7 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     hdr.w[2] = s.dtype; hdr.w[3] = s.B; hdr.w[4] = s.S; hdr.w[5] = s.C; hdr.w[6] = s.G; hdr.w[7] = s.scope;
     hdr.w[8] = (uint32_t)s.kA;
     hdr.w[14] = s.A;
+    hdr.w[15] = s.low;
     memcpy(&hdr.w[9], &cfg->budget_bits, 4);
     memcpy(&hdr.w[10], &cfg->tau, 4);
     memcpy(&hdr.w[11], &cfg->eps_l1, 4);
@@ -354,7 +370,7 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     }
 
     if (phases & TAHQ_PHASE_QUANT) {
-        dispatch<LaunchQuantPack>(s.G, s.dtype == TAHQ_BF16, d_in, packed, lay, (uint32_t)s.T, cfg->tau,
+        dispatch<LaunchQuantPack>(s.G, s.dtype == TAHQ_BF16, s.low, d_in, packed, lay, (uint32_t)s.T, cfg->tau,
                                   cfg->eps_ratio, st);
     }
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
@@ -381,7 +397,7 @@ tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t pac
     make_layout(s, &lay);
     if (packed_bytes < lay.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
     if (misaligned(d_packed) || misaligned(d_out)) return TAHQ_ERR_MISALIGNED;
-    dispatch<LaunchDecode>(s.G, out_dtype == TAHQ_BF16, static_cast<const uint8_t *>(d_packed), d_out, lay,
+    dispatch<LaunchDecode>(s.G, out_dtype == TAHQ_BF16, s.low, static_cast<const uint8_t *>(d_packed), d_out, lay,
                            (uint32_t)s.T, (uint32_t)(s.U * s.k), (hipStream_t)stream);
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
@@ -400,6 +416,7 @@ tahq_status tahq_parse_header(const void *header64, tahq_config *cfg)
     memcpy(&cfg->eps_log, &w[12], 4);
     memcpy(&cfg->eps_ratio, &w[13], 4);
     cfg->alloc_tile = w[14];
+    cfg->low_bits = w[15];
     Shape s;
     tahq_status rc = make_shape(cfg, &s);
     if (rc != TAHQ_OK) return rc;

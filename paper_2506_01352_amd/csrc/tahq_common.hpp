@@ -13,14 +13,15 @@ namespace tahq {
 
 struct Shape {
     uint32_t B, S, C, G, dtype, scope;
+    uint32_t low; // the two code widths are low and low + 1 bits (3 by default, 2 for the INT2/INT3 mix)
     uint32_t A;   // allocation tile (Sec. 3.2), a multiple of G
     uint32_t m;   // quantization tiles per allocation tile, A / G
     uint64_t T;   // quantization tiles in the tensor
     uint64_t n;   // quantization tiles per ranking unit
     uint32_t U;   // ranking units
-    uint64_t k;   // 4-bit quantization tiles per ranking unit, m * kA
+    uint64_t k;   // wide (low + 1 bit) quantization tiles per ranking unit, m * kA
     uint64_t nA;  // allocation tiles per ranking unit: what the selection ranks
-    uint64_t kA;  // 4-bit allocation tiles per ranking unit
+    uint64_t kA;  // wide allocation tiles per ranking unit
 };
 
 struct Layout {
@@ -56,13 +57,16 @@ inline uint64_t pad256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 tahq_status make_shape(const tahq_config *c, Shape *s)
 {
     if (!c) return TAHQ_ERR_NULL;
-    // a 48-byte struct is the layout from before alloc_tile was added
-    if (c->struct_size != sizeof(tahq_config) && c->struct_size != 48u) return TAHQ_ERR_INVALID_ARG;
+    // shorter structs are the layouts from before alloc_tile (48 bytes) and low_bits (52 bytes) were added
+    if (c->struct_size != sizeof(tahq_config) && c->struct_size != 48u && c->struct_size != 52u)
+        return TAHQ_ERR_INVALID_ARG;
     const uint32_t A = (c->struct_size == 48u || c->alloc_tile == 0) ? c->tile : c->alloc_tile;
+    const uint32_t low = (c->struct_size < 56u || c->low_bits == 0) ? 3u : c->low_bits;
+    if (low != 2u && low != 3u) return TAHQ_ERR_INVALID_ARG;
     if (c->batch == 0 || c->seq == 0 || c->hidden == 0) return TAHQ_ERR_INVALID_ARG;
     if (c->tile == 0 || c->hidden % c->tile != 0) return TAHQ_ERR_INVALID_ARG;
     if (c->dtype > TAHQ_BF16 || c->scope > 1) return TAHQ_ERR_INVALID_ARG;
-    if (!(c->budget_bits >= 3.0f && c->budget_bits <= 4.0f)) return TAHQ_ERR_INVALID_ARG;
+    if (!(c->budget_bits >= (float)low && c->budget_bits <= (float)(low + 1u))) return TAHQ_ERR_INVALID_ARG;
     if (A % c->tile != 0 || c->hidden % A != 0) return TAHQ_ERR_INVALID_ARG;
     if (c->tile != 32 && c->tile != 64 && c->tile != 128) return TAHQ_ERR_UNSUPPORTED;
     uint64_t M = c->hidden / c->tile;
@@ -71,13 +75,14 @@ tahq_status make_shape(const tahq_config *c, Shape *s)
     s->B = c->batch; s->S = c->seq; s->C = c->hidden; s->G = c->tile;
     s->dtype = c->dtype; s->scope = c->scope;
     s->T = T;
+    s->low = low;
     s->A = A;
     s->m = A / c->tile;
     s->n = c->scope ? T : (uint64_t)c->seq * M;
     s->U = c->scope ? 1u : c->batch;
     s->nA = s->n / s->m;
     double n = (double)s->nA;
-    double k = __builtin_floor((double)c->budget_bits * n - 3.0 * n + 0.5);
+    double k = __builtin_floor((double)c->budget_bits * n - (double)low * n + 0.5);
     if (k < 0) k = 0;
     if (k > n) k = n;
     s->kA = (uint64_t)k;
@@ -93,7 +98,7 @@ void make_layout(const Shape &s, Layout *L)
     L->scale = L->pivot + pad64(s.T);
     L->zero = L->scale + pad64(2 * s.T);
     L->payload = L->zero + pad64(2 * s.T);
-    L->total = L->payload + (uint64_t)(s.G / 8) * (3 * s.T + (uint64_t)s.U * s.k);
+    L->total = L->payload + (uint64_t)(s.G / 8) * (s.low * s.T + (uint64_t)s.U * s.k);
 }
 
 void make_workspace(const Shape &s, Workspace *w)

@@ -467,18 +467,18 @@ __device__ __forceinline__ void load_meta(const uint8_t *__restrict__ packed, co
     m.rank0 = ranks[j0 >> 6];
 }
 
-// Width of my tile, its payload position inside the batch (in units of G/8 bytes), and the number of
-// 4-bit tiles in the batch.
-template <int TILES>
+// Width of my tile (LOW or LOW + 1 bits), its payload position inside the batch (in units of G/8 bytes), and
+// the number of wide tiles in the batch.
+template <int TILES, int LOW>
 __device__ __forceinline__ void tile_pos(const BatchMeta<TILES> &m, int tid, uint32_t *b, uint32_t *rel, uint32_t *total4)
 {
-    uint32_t bb = 3, rr = 0, tot = 0;
+    uint32_t bb = LOW, rr = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < BatchMeta<TILES>::WORDS; ++w) {
         if (w == (tid >> 6)) {
             const uint32_t bit = (uint32_t)tid & 63u;
-            bb = 3u + (uint32_t)((m.word[w] >> bit) & 1ull);
-            rr = 3u * (uint32_t)tid + tot + (uint32_t)__popcll(m.word[w] & ((1ull << bit) - 1ull));
+            bb = (uint32_t)LOW + (uint32_t)((m.word[w] >> bit) & 1ull);
+            rr = (uint32_t)LOW * (uint32_t)tid + tot + (uint32_t)__popcll(m.word[w] & ((1ull << bit) - 1ull));
         }
         tot += (uint32_t)__popcll(m.word[w]);
     }
@@ -536,11 +536,42 @@ __device__ __forceinline__ void transform_row(const uint8_t *row, bool flag, flo
     }
 }
 
+// The tile's LSB-first bit string, as dwords, from groups of four W-bit codes (g4[g] = q0 + 2^W q1 + 2^2W q2
+// + 2^3W q3).  Dwords past the string are zero.
+template <int G, int W>
+__device__ __forceinline__ void pack_groups(const uint32_t *g4, uint32_t *dw)
+{
+    if constexpr (W == 4) {
+#pragma unroll
+        for (int i = 0; i < G / 8; ++i) dw[i] = g4[2 * i] | (g4[2 * i + 1] << 16);
+    } else if constexpr (W == 3) {
+        // 12-bit groups: eight of them fill three dwords
+#pragma unroll
+        for (int i = 0; i < G / 32; ++i) {
+            const uint32_t *p = g4 + 8 * i;
+            dw[3 * i + 0] = p[0] | (p[1] << 12) | (p[2] << 24);
+            dw[3 * i + 1] = (p[2] >> 8) | (p[3] << 4) | (p[4] << 16) | (p[5] << 28);
+            dw[3 * i + 2] = (p[5] >> 4) | (p[6] << 8) | (p[7] << 20);
+        }
+#pragma unroll
+        for (int i = 3 * (G / 32); i < G / 8; ++i) dw[i] = 0;
+    } else {
+        static_assert(W == 2, "code widths are 2, 3 or 4 bits");
+        // 8-bit groups: four of them fill a dword
+#pragma unroll
+        for (int i = 0; i < G / 16; ++i)
+            dw[i] = g4[4 * i] | (g4[4 * i + 1] << 8) | (g4[4 * i + 2] << 16) | (g4[4 * i + 3] << 24);
+#pragma unroll
+        for (int i = G / 16; i < G / 8; ++i) dw[i] = 0;
+    }
+}
+
 // Step 2: range, quantizer parameters, codes, and the tile's LSB-first bit string written as b units at
-// `dst` (LDS).  Returns scale | zero << 16.
-template <int G>
+// `dst` (LDS); b is LOW or LOW + 1.  Returns scale | zero << 16.
+template <int G, int LOW>
 __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, typename Unit<G>::type *dst)
 {
+    constexpr uint32_t WIDE = LOW + 1;
     float mn = fmin3(x[0], x[1], x[2]), mx = fmax3(x[0], x[1], x[2]);
 #pragma unroll
     for (int k = 3; k + 1 < G; k += 2) { mn = fmin3(mn, x[k], x[k + 1]); mx = fmax3(mx, x[k], x[k + 1]); }
@@ -548,7 +579,7 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
     mx = __builtin_fmaxf(mx, x[G - 1]) + 0.0f;
 
     // asymmetric quantizer, binary16 metadata rounded outwards
-    const float Lv = (b == 4u) ? 15.0f : 7.0f;
+    const float Lv = (b == WIDE) ? (float)((1u << WIDE) - 1u) : (float)((1u << LOW) - 1u);
     const uint32_t z16 = f16_down(mn);
     const float mnf = f16_widen(z16);
     const float s = (mx - mnf) / Lv;
@@ -558,7 +589,7 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
     const float rcp = 1.0f / sf;
 
     // codes, four at a time: q0 + m q1 + m^2 q2 + m^3 q3 is an exact integer below 2^16 in fp32
-    const float m1 = (b == 4u) ? 16.0f : 8.0f;
+    const float m1 = (b == WIDE) ? (float)(1u << WIDE) : (float)(1u << LOW);
     const float m2 = m1 * m1, m3 = m2 * m1;
     // Every element lies in [mn, mx]; if z <= mn, (x - z) * rcp lies in [0, (mx - z) * rcp], and when that
     // bound rounds to at most L the clamp is the identity and is skipped.  Both conditions can fail only when
@@ -586,24 +617,11 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
     }
     // LSB-first bit string of the tile as dwords
     uint32_t dw[G / 8];
-    if (b == 4u) {
+    if (b == WIDE) pack_groups<G, WIDE>(g4, dw);
+    else pack_groups<G, LOW>(g4, dw);
 #pragma unroll
-        for (int i = 0; i < G / 8; ++i) dw[i] = g4[2 * i] | (g4[2 * i + 1] << 16);
-    } else {
-        // 12-bit groups: eight of them fill three dwords
-#pragma unroll
-        for (int i = 0; i < G / 32; ++i) {
-            const uint32_t *p = g4 + 8 * i;
-            dw[3 * i + 0] = p[0] | (p[1] << 12) | (p[2] << 24);
-            dw[3 * i + 1] = (p[2] >> 8) | (p[3] << 4) | (p[4] << 16) | (p[5] << 28);
-            dw[3 * i + 2] = (p[5] >> 4) | (p[6] << 8) | (p[7] << 20);
-        }
-#pragma unroll
-        for (int i = 3 * (G / 32); i < G / 8; ++i) dw[i] = 0;
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        if (u < 3 || b == 4u) {
+    for (int u = 0; u < (int)WIDE; ++u) {
+        if (u < LOW || b == WIDE) {
             if constexpr (G == 32) dst[u] = dw[u];
             else if constexpr (G == 64) dst[u] = make_uint2(dw[2 * u], dw[2 * u + 1]);
             else dst[u] = make_uint4(dw[4 * u], dw[4 * u + 1], dw[4 * u + 2], dw[4 * u + 3]);
@@ -624,7 +642,7 @@ struct QuantPackOccupancy { static constexpr int WAVES_PER_SIMD = (G * ESIZE <= 
 // paths rarely both run.  The payload buffer reuses the rows' LDS once every lane holds its tile in
 // registers, which keeps the workgroup small enough for four to share a compute unit: this kernel
 // lives on the loads of its neighbours being in flight while it computes.
-template <int G, bool BF16>
+template <int G, bool BF16, int LOW>
 __global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES), (QuantPackOccupancy<G, BF16 ? 2 : 4>::WAVES_PER_SIMD))
 void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Layout lay, uint32_t T, float tau,
                   float eps_ratio)
@@ -633,9 +651,10 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     using B = Batch<G, ES>;
     using U = typename Unit<G>::type;
     constexpr int WAVES = (B::TILES + 63) / 64;
-    static_assert(sizeof(U) * 4 * B::TILES <= (size_t)B::LDS_BYTES, "payload buffer must fit in the rows");
+    constexpr uint32_t WIDE = LOW + 1;           // the two code widths are LOW and WIDE bits
+    static_assert(sizeof(U) * WIDE * B::TILES <= (size_t)B::LDS_BYTES, "payload buffer must fit in the rows");
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
-    __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == 4) << 8 | rel << 9
+    __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == WIDE) << 8 | rel << 9
     __shared__ uint16_t order[B::TILES];         // tiles in class order
     __shared__ uint32_t class_count[WAVES][4];
     U *pay = reinterpret_cast<U *>(lds);         // valid only after every lane has left the rows
@@ -653,7 +672,7 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     if (full) store_batch<G, ES, true>(v, nvalid, lds);
     else store_batch<G, ES, false>(v, nvalid, lds);
     uint32_t b, rel, total4;
-    tile_pos<B::TILES>(meta, tid, &b, &rel, &total4);
+    tile_pos<B::TILES, LOW>(meta, tid, &b, &rel, &total4);
     __syncthreads();
 
     // round 1: my own tile
@@ -661,8 +680,8 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     uint32_t cls = 4;                            // tiles past the end sort last
     if (valid) {
         const uint32_t pv = analyse_row<G, BF16>(lds + tid * B::STRIDE, tau, eps_ratio);
-        info[tid] = pv | ((b == 4u) ? 0x100u : 0u) | (rel << 9);
-        cls = ((pv >> 7) << 1) | (b == 4u ? 1u : 0u);
+        info[tid] = pv | ((b == WIDE) ? 0x100u : 0u) | (rel << 9);
+        cls = ((pv >> 7) << 1) | (b == WIDE ? 1u : 0u);
     }
     uint32_t rank_in_wave = 0;
 #pragma unroll
@@ -693,7 +712,7 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     }
     __syncthreads();                             // the rows are dead: their LDS becomes the payload buffer
     if (valid) {
-        const uint32_t meta16 = quantize_values<G>(x, (inf & 0x100u) ? 4u : 3u, pay + (inf >> 9));
+        const uint32_t meta16 = quantize_values<G, LOW>(x, (inf & 0x100u) ? WIDE : (uint32_t)LOW, pay + (inf >> 9));
         const uint64_t j = j0 + t;
         reinterpret_cast<uint16_t *>(packed + lay.scale)[j] = (uint16_t)meta16;
         reinterpret_cast<uint16_t *>(packed + lay.zero)[j] = (uint16_t)(meta16 >> 16);
@@ -702,10 +721,10 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     __syncthreads();
 
     // the batch's payload is one contiguous span: copy it out unit by unit, coalesced
-    const uint32_t span = 3u * nvalid + total4;
-    U *gdst = reinterpret_cast<U *>(packed + lay.payload) + (3ull * j0 + meta.rank0);
+    const uint32_t span = (uint32_t)LOW * nvalid + total4;
+    U *gdst = reinterpret_cast<U *>(packed + lay.payload) + ((uint64_t)LOW * j0 + meta.rank0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < (int)WIDE; ++i) {
         const uint32_t q = (uint32_t)i * B::TILES + tid;
         if (q < span) gdst[q] = pay[q];
     }
@@ -713,29 +732,14 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
 
 // ------------------------------------------------------------- K4: decode
 
-// Alg. 1 step 5 for my tile: my 3 or 4 payload units at `src` (LDS) -> codes -> q*s + z -> for
-// transformed tiles the butterfly, 1/sqrt(G) and P_d -> my LDS row in the output type.
-template <int G, bool OUT_BF16>
-__device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, uint32_t b, uint32_t s16, uint32_t z16,
-                                           uint32_t pv, uint8_t *row)
+// The tile's W-bit codes brought onto nibble boundaries: nib[i] holds codes 8i .. 8i+7, one per nibble.
+template <int G, int W>
+__device__ __forceinline__ void codes_to_nibbles(const uint32_t *dw, uint32_t *nib)
 {
-    using U = typename Unit<G>::type;
-    const float sf = f16_widen(s16), mnf = f16_widen(z16);
-    // my 3 or 4 units (the 4th is read in any case: it stays inside the array)
-    uint32_t dw[G / 8];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const U t = src[u];
-        if constexpr (G == 32) dw[u] = t;
-        else if constexpr (G == 64) { dw[2 * u] = t.x; dw[2 * u + 1] = t.y; }
-        else { dw[4 * u] = t.x; dw[4 * u + 1] = t.y; dw[4 * u + 2] = t.z; dw[4 * u + 3] = t.w; }
-    }
-    // bring three-bit codes onto nibble boundaries: 24 bits (8 codes) -> 32 bits
-    uint32_t nib[G / 8];
-    if (b == 4u) {
+    if constexpr (W == 4) {
 #pragma unroll
         for (int i = 0; i < G / 8; ++i) nib[i] = dw[i];
-    } else {
+    } else if constexpr (W == 3) {
 #pragma unroll
         for (int i = 0; i < G / 8; ++i) {
             // codes 8i .. 8i+7 occupy bits [24i, 24i+24) of the string
@@ -748,7 +752,43 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
             t = (t & 0x07070707u) | ((t & 0x38383838u) << 1);
             nib[i] = t;
         }
+    } else {
+        static_assert(W == 2, "code widths are 2, 3 or 4 bits");
+#pragma unroll
+        for (int i = 0; i < G / 8; ++i) {
+            // codes 8i .. 8i+7 occupy bits [16i, 16i+16) of the string
+            uint32_t t = (dw[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+            t = (t & 0x000000ffu) | ((t & 0x0000ff00u) << 8);
+            t = (t & 0x000f000fu) | ((t & 0x00f000f0u) << 4);
+            t = (t & 0x03030303u) | ((t & 0x0c0c0c0cu) << 2);
+            nib[i] = t;
+        }
     }
+}
+
+// Alg. 1 step 5 for my tile: my LOW or LOW + 1 payload units at `src` (LDS) -> codes -> q*s + z -> for
+// transformed tiles the butterfly, 1/sqrt(G) and P_d -> my LDS row in the output type.
+template <int G, bool OUT_BF16, int LOW>
+__device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, uint32_t b, uint32_t s16, uint32_t z16,
+                                           uint32_t pv, uint8_t *row)
+{
+    using U = typename Unit<G>::type;
+    constexpr int WIDE = LOW + 1;
+    const float sf = f16_widen(s16), mnf = f16_widen(z16);
+    // my LOW or WIDE units (the last one is read in any case: it stays inside the array)
+    uint32_t dw[G / 8];
+#pragma unroll
+    for (int i = 0; i < G / 8; ++i) dw[i] = 0;
+#pragma unroll
+    for (int u = 0; u < WIDE; ++u) {
+        const U t = src[u];
+        if constexpr (G == 32) dw[u] = t;
+        else if constexpr (G == 64) { dw[2 * u] = t.x; dw[2 * u + 1] = t.y; }
+        else { dw[4 * u] = t.x; dw[4 * u + 1] = t.y; dw[4 * u + 2] = t.z; dw[4 * u + 3] = t.w; }
+    }
+    uint32_t nib[G / 8];
+    if (b == (uint32_t)WIDE) codes_to_nibbles<G, WIDE>(dw, nib);
+    else codes_to_nibbles<G, LOW>(dw, nib);
     // de-quantize: even codes sit in the low nibbles of the bytes, odd codes in the high nibbles
     // (scaled by 16, undone exactly by a scale of sf/16)
     const float sf16 = sf * 0.0625f;
@@ -808,7 +848,7 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
 // The only two-step dependency -- the rank-table entries that locate a batch's payload and give its length
 // -- is taken out of the loop: the entries of the workgroup's batches are read into LDS up front.
 // The ragged last batch is handled after the loop by one workgroup.
-template <int G, bool OUT_BF16>
+template <int G, bool OUT_BF16, int LOW>
 __global__ __launch_bounds__((Batch<G, OUT_BF16 ? 2 : 4>::TILES))
 void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout lay, uint32_t T, uint32_t total_four_bit)
 {
@@ -817,10 +857,11 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     using U = typename Unit<G>::type;
     using Meta = BatchMeta<B::TILES>;
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
-    __shared__ __attribute__((aligned(16))) U pay[B::TILES * 4];
+    constexpr uint32_t WIDE = LOW + 1;           // the two code widths are LOW and WIDE bits
+    __shared__ __attribute__((aligned(16))) U pay[B::TILES * WIDE];
     __shared__ uint32_t rank_lds[B::TILES + 1];
     constexpr int WAVES = (B::TILES + 63) / 64;
-    __shared__ uint2 tile_meta[B::TILES];        // per tile: scale | zero << 16, pivot byte | (b == 4) << 8 | rel << 9
+    __shared__ uint2 tile_meta[B::TILES];        // per tile: scale | zero << 16, pivot byte | (b == WIDE) << 8 | rel << 9
     __shared__ uint16_t order[B::TILES];         // tiles in class order
     __shared__ uint32_t class_count[WAVES][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -852,19 +893,19 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     if (first < last) load_rank_window(wfirst);
 
     Meta m;            // bit map words of the batch whose loads are in flight / have just arrived
-    U pre[4];
+    U pre[WIDE];
     uint32_t s16 = 0, z16 = 0, pv = 0;
     // issue the loads of full batch `batch` (inside the current window)
     auto fetch = [&](uint32_t batch) {
         const uint64_t j0 = (uint64_t)batch * B::TILES;
         m.rank0 = rank_lds[batch - wfirst];
         const uint32_t total4 = rank_lds[batch - wfirst + 1] - m.rank0;
-        const uint64_t base = 3ull * j0 + m.rank0;
+        const uint64_t base = (uint64_t)LOW * j0 + m.rank0;
 #pragma unroll
-        for (int i = 0; i < 3; ++i) pre[i] = payload[base + (uint32_t)i * B::TILES + tid];
-        // a thread's fourth unit exists only if the batch has more than `tid` four-bit tiles; otherwise the
+        for (int i = 0; i < LOW; ++i) pre[i] = payload[base + (uint32_t)i * B::TILES + tid];
+        // a thread's last unit exists only if the batch has more than `tid` wide tiles; otherwise the
         // load is pointed at the batch's first unit (a line that is being read anyway) and ignored
-        pre[3] = payload[base + ((uint32_t)tid < total4 ? 3u * (uint32_t)B::TILES + (uint32_t)tid : 0u)];
+        pre[LOW] = payload[base + ((uint32_t)tid < total4 ? (uint32_t)LOW * (uint32_t)B::TILES + (uint32_t)tid : 0u)];
 #pragma unroll
         for (int w = 0; w < Meta::WORDS; ++w) m.word[w] = bitmap[(j0 >> 6) + w];
         s16 = scale[j0 + tid];
@@ -877,13 +918,13 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     uint32_t prev_batch = 0;
     for (uint32_t batch = first; batch < last; ++batch) {
         uint32_t b, rel, total4;
-        tile_pos<B::TILES>(m, tid, &b, &rel, &total4);
+        tile_pos<B::TILES, LOW>(m, tid, &b, &rel, &total4);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pay[(uint32_t)i * B::TILES + tid] = pre[i];
+        for (int i = 0; i < (int)WIDE; ++i) pay[(uint32_t)i * B::TILES + tid] = pre[i];
         // Tiles are regrouped by class -- (plain | transformed) x (3 | 4 bit) -- as in the encoder: lane p decodes
         // the p-th tile in class order, so the butterfly runs only in the wavefronts that hold transformed tiles.
-        tile_meta[tid] = make_uint2(s16 | (z16 << 16), pv | ((b == 4u) ? 0x100u : 0u) | (rel << 9));
-        const uint32_t cls = ((pv >> 7) << 1) | (b == 4u ? 1u : 0u);
+        tile_meta[tid] = make_uint2(s16 | (z16 << 16), pv | ((b == WIDE) ? 0x100u : 0u) | (rel << 9));
+        const uint32_t cls = ((pv >> 7) << 1) | (b == WIDE ? 1u : 0u);
         uint32_t rank_in_wave = 0;
 #pragma unroll
         for (uint32_t c = 0; c < 4; ++c) {
@@ -915,8 +956,8 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         {
             const uint32_t t = order[tid];
             const uint2 tm = tile_meta[t];
-            decode_row<G, OUT_BF16>(pay + (tm.y >> 9), (tm.y & 0x100u) ? 4u : 3u, tm.x & 0xffffu, tm.x >> 16, tm.y & 0xffu,
-                                    lds + t * B::STRIDE);
+            decode_row<G, OUT_BF16, LOW>(pay + (tm.y >> 9), (tm.y & 0x100u) ? WIDE : (uint32_t)LOW, tm.x & 0xffffu,
+                                         tm.x >> 16, tm.y & 0xffu, lds + t * B::STRIDE);
         }
         prev_batch = batch;
         have_prev = true;
@@ -929,13 +970,13 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         const uint64_t j0 = (uint64_t)nfull * B::TILES;
         load_meta<B::TILES>(packed, lay, j0, T, 0u, m);
         uint32_t b, rel, total4;
-        tile_pos<B::TILES>(m, tid, &b, &rel, &total4);
-        const uint32_t span = 3u * tail + total4;
-        const U *gsrc = payload + (3ull * j0 + m.rank0);
+        tile_pos<B::TILES, LOW>(m, tid, &b, &rel, &total4);
+        const uint32_t span = (uint32_t)LOW * tail + total4;
+        const U *gsrc = payload + ((uint64_t)LOW * j0 + m.rank0);
         for (uint32_t q = tid; q < span; q += B::TILES) pay[q] = gsrc[q];
         __syncthreads();
         if ((uint32_t)tid < tail)
-            decode_row<G, OUT_BF16>(pay + rel, b, scale[j0 + tid], zero[j0 + tid], pivot[j0 + tid], row);
+            decode_row<G, OUT_BF16, LOW>(pay + rel, b, scale[j0 + tid], zero[j0 + tid], pivot[j0 + tid], row);
         __syncthreads();
         stage_out<G, ES, false>(out, j0, tail, lds);
     }

@@ -31,15 +31,18 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_sizes_match_the_oracle_layout_on_all_configs_and_variants():
-    cases = [(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits, 0, 0) for w in workloads.CONFIGS]
-    cases += [(3, 7, 96, 32, 0, 3.3, 0, 0), (3, 7, 96, 32, 0, 3.3, 1, 0), (1, 1, 128, 128, 1, 3.5, 0, 0),
-              (2, 5, 640, 64, 1, 3.01, 0, 0)]
+    cases = [(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits, 0, 0, 0) for w in workloads.CONFIGS]
+    cases += [(3, 7, 96, 32, 0, 3.3, 0, 0, 0), (3, 7, 96, 32, 0, 3.3, 1, 0, 0), (1, 1, 128, 128, 1, 3.5, 0, 0, 0),
+              (2, 5, 640, 64, 1, 3.01, 0, 0, 0)]
     # allocation tiles of several quantization tiles, up to the whole token
-    cases += [(3, 7, 96, 32, 0, 3.3, 0, 96), (3, 7, 96, 32, 0, 3.3, 1, 32), (2, 5, 640, 64, 1, 3.4, 0, 320),
-              (8, 4096, 8192, 64, 1, 3.25, 0, 8192), (8, 4096, 8192, 64, 1, 3.25, 0, 128)]
-    for B, S, Cc, G, dt, bud, scope, A in cases:
-        cfg = tahq.make_config(B, S, Cc, G, dt, bud, scope=scope, alloc_tile=A)
-        ocfg = o32.make_cfg(B, S, Cc, G, dt, bud, scope=scope, alloc_tile=A)
+    cases += [(3, 7, 96, 32, 0, 3.3, 0, 96, 0), (3, 7, 96, 32, 0, 3.3, 1, 32, 0), (2, 5, 640, 64, 1, 3.4, 0, 320, 0),
+              (8, 4096, 8192, 64, 1, 3.25, 0, 8192, 0), (8, 4096, 8192, 64, 1, 3.25, 0, 128, 0)]
+    # the INT2/INT3 mix
+    cases += [(3, 7, 96, 32, 0, 2.3, 0, 0, 2), (8, 4096, 8192, 64, 1, 2.2, 0, 0, 2), (2, 5, 640, 64, 1, 3.0, 0, 320, 2),
+              (2, 5, 640, 128, 1, 2.0, 1, 0, 2), (2, 5, 640, 64, 1, 3.4, 0, 0, 3)]
+    for B, S, Cc, G, dt, bud, scope, A, low in cases:
+        cfg = tahq.make_config(B, S, Cc, G, dt, bud, scope=scope, alloc_tile=A, low_bits=low)
+        ocfg = o32.make_cfg(B, S, Cc, G, dt, bud, scope=scope, alloc_tile=A, low_bits=low)
         assert tahq.tahq_packed_size(cfg) == o32.packed_size(ocfg) > 0
         assert tahq.tahq_k_per_unit(cfg) == o32.k_per_unit(ocfg)
         assert tahq.tahq_workspace_size(cfg) > 0
@@ -47,7 +50,7 @@ def test_sizes_match_the_oracle_layout_on_all_configs_and_variants():
 
 def test_defaults_and_version():
     cfg = tahq.tahq_config_default()
-    assert cfg.struct_size == C.sizeof(tahq.tahq_config) == 52 and cfg.alloc_tile == 0
+    assert cfg.struct_size == C.sizeof(tahq.tahq_config) == 56 and cfg.alloc_tile == 0 and cfg.low_bits == 0
     assert (cfg.tile, cfg.tau, cfg.scope) == (64, 2.0, 0)
     assert abs(cfg.budget_bits - 3.8) < 1e-6 and abs(cfg.eps_log - 1e-8) < 1e-12
     assert tahq.tahq_version() >> 16 == 1
@@ -60,6 +63,8 @@ def test_invalid_configs_are_rejected_with_size_zero():
         dict(batch=0), dict(seq=0), dict(hidden=0), dict(hidden=100), dict(tile=16), dict(tile=48),
         dict(budget_bits=2.9), dict(budget_bits=4.1), dict(budget_bits=float("nan")), dict(dtype=2), dict(scope=2),
         dict(alloc_tile=32), dict(alloc_tile=96), dict(alloc_tile=192), dict(alloc_tile=512),
+        dict(low_bits=1), dict(low_bits=4), dict(low_bits=2), dict(low_bits=2, budget_bits=3.1),
+        dict(low_bits=2, budget_bits=1.9),
     ]
     for kw in bad:
         args = dict(batch=2, seq=4, hidden=256, tile=64, dtype=0, budget_bits=3.5)
@@ -74,6 +79,11 @@ def test_invalid_configs_are_rejected_with_size_zero():
     assert tahq.tahq_packed_size(cfg) == 0
     cfg.struct_size = 48
     assert tahq.tahq_packed_size(cfg) == tahq.tahq_packed_size(tahq.make_config(2, 4, 256, 64, 0, 3.5)) > 0
+    # ... and the 52-byte layout from before low_bits existed
+    cfg = tahq.make_config(2, 4, 256, 64, 0, 3.5, alloc_tile=128, low_bits=7)
+    assert tahq.tahq_packed_size(cfg) == 0
+    cfg.struct_size = 52
+    assert tahq.tahq_packed_size(cfg) == tahq.tahq_packed_size(tahq.make_config(2, 4, 256, 64, 0, 3.5, alloc_tile=128)) > 0
 
 
 def _call_encode(cfg, d_in, d_packed, cap, d_ws, wcap):
@@ -129,7 +139,11 @@ def test_parse_header_round_trips_an_oracle_stream():
     wide = o32.encode(ocfg, x)
     cfg = tahq.tahq_parse_header(wide[:64].tobytes())
     assert cfg.alloc_tile == 512 and tahq.tahq_packed_size(cfg) == wide.size
-    assert tahq.tahq_k_per_unit(cfg) == o32.k_per_unit(ocfg) == 4
+    assert tahq.tahq_k_per_unit(cfg) == o32.k_per_unit(ocfg) == 4 and cfg.low_bits == 3
+    ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, 2.25, low_bits=2)
+    narrow = o32.encode(ocfg, x)
+    cfg = tahq.tahq_parse_header(narrow[:64].tobytes())
+    assert cfg.low_bits == 2 and cfg.budget_bits == 2.25 and tahq.tahq_packed_size(cfg) == narrow.size
     broken = packed[:64].copy(); broken[0] = ord("X")
     with pytest.raises(tahq.TahqError):
         tahq.tahq_parse_header(broken.tobytes())

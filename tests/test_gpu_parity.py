@@ -86,11 +86,11 @@ def first_diff(a, b):
     return None if idx.size == 0 else int(idx[0])
 
 
-def compare_streams(got, want, T, G, n_units, k):
+def compare_streams(got, want, T, G, n_units, k, low=3):
     """Byte-exact comparison with a section-by-section report on failure."""
     if np.array_equal(got, want):
         return
-    off = o64.section_offsets(T, G, n_units, k)
+    off = o64.section_offsets(T, G, n_units, k, low)
     names = ["bitmap", "ranks", "pivot", "scale", "zero", "payload", "total"]
     report = []
     if not np.array_equal(got[:64], want[:64]):
@@ -118,7 +118,7 @@ def check_case(tahq, x, B, S, Cc, G, dtype, budget, out_dtype=None, **kw):
         f"allocation-tile entropy bits differ at {first_diff(HA.view(np.uint32), wantHA.view(np.uint32))}"
     want = o32.encode(ocfg, x)
     n_units = 1 if kw.get("scope", 0) else B
-    compare_streams(packed, want, T, G, n_units, o32.k_per_unit(ocfg) * o32.tiles_per_alloc(ocfg))
+    compare_streams(packed, want, T, G, n_units, o32.k_per_unit(ocfg) * o32.tiles_per_alloc(ocfg), o32.low_bits(ocfg))
     want_out = o32.decode(ocfg, want, out_dtype)
     if out_dtype == tahq.F32:
         fin = np.isfinite(want_out)
@@ -227,6 +227,28 @@ def test_allocation_tile_ties_and_many_small_units(tahq):
     check_case(tahq, y, 300, 3, 128, 64, tahq.F32, 3.34, alloc_tile=128)
 
 
+# the INT2/INT3 mix of the appendix on bit allocation (low_bits = 2)
+@pytest.mark.parametrize("index,shape", SMALL)
+@pytest.mark.parametrize("budget", (2.2, 2.0, 3.0))
+def test_int2_int3_mix_bit_exact(tahq, index, shape, budget):
+    w, x = workloads.generate(index, **shape)
+    _say(f"[case] {w.name} shape={w.batch}x{w.seq}x{w.hidden} INT2/INT3 budget={budget}")
+    check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, low_bits=2)
+
+
+@pytest.mark.parametrize("G", (32, 64, 128))
+def test_int2_int3_edge_tiles_other_output_type_and_allocation_tiles(tahq, G):
+    tiles = workloads.edge_tiles(G)
+    n = len(tiles) // 3 * 3
+    _say(f"[case] INT2/INT3 edge tiles G={G}")
+    for budget in (2.0, 2.5, 3.0):
+        check_case(tahq, tiles, 1, len(tiles), G, G, tahq.F32, budget, low_bits=2)
+        check_case(tahq, workloads.f32_to_bf16_bits(tiles), 1, len(tiles), G, G, tahq.BF16, budget, out_dtype=tahq.F32,
+                   low_bits=2)
+    check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, 2.4, out_dtype=tahq.BF16, low_bits=2, alloc_tile=3 * G)
+    check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, 2.4, low_bits=2, scope=1, tau=4.0)
+
+
 def test_massive_entropy_ties_are_broken_by_index(tahq):
     # config-5-like tensor (20% all-zero tokens: entropy exactly 0) with a budget that puts the
     # threshold inside the tie, plus a tensor whose tiles are all identical
@@ -312,6 +334,25 @@ def test_full_size_configs_bit_exact(tahq, index):
     got = got.numpy() if w.dtype == tahq.F32 else got.view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(got.view(np.uint32 if w.dtype == tahq.F32 else np.uint16),
                           want_out.view(np.uint32 if w.dtype == tahq.F32 else np.uint16))
+
+
+def test_full_size_int2_int3_mix_bit_exact(tahq):
+    # the headline tensor at 80% INT2 + 20% INT3 (the appendix's setting)
+    w, x = workloads.generate(4)
+    d_in = to_device(x)
+    T = w.elements // w.tile
+    _say(f"[case] full size {w.name} INT2/INT3 budget 2.2")
+    cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, 2.2, low_bits=2)
+    ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, 2.2, low_bits=2)
+    codec = tahq.Codec(cfg)
+    codec.encode(d_in)
+    codec.decode()
+    torch.cuda.synchronize()
+    want = o32.encode(ocfg, x)
+    compare_streams(codec.packed.cpu().numpy(), want, T, w.tile, w.batch, o32.k_per_unit(ocfg), 2)
+    want_out = o32.decode(ocfg, want, w.dtype)
+    got = codec.out.cpu().view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want_out)
 
 
 def test_full_size_token_level_allocation_bit_exact(tahq):
