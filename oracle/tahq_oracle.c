@@ -54,7 +54,7 @@ static int cfg_ok(const tahq_oracle_cfg *c)
 {
     if (!c) return 0;
     if (c->batch == 0 || c->seq == 0 || c->hidden == 0) return 0;
-    if (c->tile != 32 && c->tile != 64 && c->tile != 128) return 0;
+    if (c->tile != 8 && c->tile != 16 && c->tile != 32 && c->tile != 64 && c->tile != 128) return 0;
     if (c->hidden % c->tile) return 0;
     if (c->dtype > 1 || c->scope > 1) return 0;
     if (c->low_bits != 0 && c->low_bits != 2 && c->low_bits != 3) return 0;
@@ -286,10 +286,16 @@ void tahq_oracle_butterfly(float *v, uint32_t G)
             }
 }
 
-/* fp32(1/sqrt(G)) for the three supported tile widths. */
+/* fp32(1/sqrt(G)) for the supported tile widths. */
 static float c_G(uint32_t G)
 {
-    return G == 32 ? 0x1.6a09e6p-3f : (G == 64 ? 0.125f : 0x1.6a09e6p-4f);
+    switch (G) {
+    case 8: return 0x1.6a09e6p-2f;
+    case 16: return 0.25f;
+    case 32: return 0x1.6a09e6p-3f;
+    case 64: return 0.125f;
+    default: return 0x1.6a09e6p-4f;      /* 128 */
+    }
 }
 
 /* Sec. 3.3, Eq. 4: alpha P_d (1/sqrt(G)) H_G.  P_d swaps coordinates 1 and d. */

@@ -27,7 +27,8 @@ MUTATIONS = [
      "for (uint32_t q = 0; q < m; ++q) width[(u * n + it[r].j) * m + q] = (uint8_t)((r < k && q == 0) ? lo + 1 : lo);"),
     ("log polynomial coefficient off by 2x", "0x1.c4859ep+2f", "0x1.c4859ep+1f"),
     ("butterfly difference with swapped operands", "v[j + h] = x - y;", "v[j + h] = y - x;"),
-    ("wrong 1/sqrt(G) for G = 64", "(G == 64 ? 0.125f :", "(G == 64 ? 0.25f :"),
+    ("wrong 1/sqrt(G) for G = 64", "case 64: return 0.125f;", "case 64: return 0.25f;"),
+    ("wrong 1/sqrt(G) for G = 8", "case 8: return 0x1.6a09e6p-2f;", "case 8: return 0x1.6a09e6p-3f;"),
     ("pivot swapped with coordinate 2 instead of 1",
      "    float t = v[0]; v[0] = v[d]; v[d] = t;\n    tahq_oracle_butterfly(v, G);\n    float c = c_G(G);",
      "    float t = v[1]; v[1] = v[d]; v[d] = t;\n    tahq_oracle_butterfly(v, G);\n    float c = c_G(G);"),

@@ -14,7 +14,7 @@ from scipy.linalg import hadamard
 import workloads
 from oracle import o32, o64
 
-GS = (32, 64, 128)
+GS = (8, 16, 32, 64, 128)
 
 
 # ---------------------------------------------------------------- Hadamard
@@ -125,7 +125,7 @@ def test_entropy_closed_forms(G):
     onehot = np.zeros(G, np.float32); onehot[G // 2] = -7.0
     assert abs(o32.entropy(onehot)) < tol
     assert o32.entropy(np.zeros(G, np.float32)) == 0.0
-    for m in (2, 4, 8, 16):
+    for m in (2, 4, 8, min(16, G)):
         v = np.zeros(G, np.float32); v[:m] = 3.0; v[1] = -3.0
         assert abs(o32.entropy(v) - math.log(m)) < tol
 
@@ -383,7 +383,7 @@ def test_allocation_tile_entropy_closed_forms_and_float64_definition(G, m):
 
 def test_allocation_tile_of_one_quantization_tile_is_the_default():
     rng = np.random.default_rng(32)
-    for G in (32, 64, 128):
+    for G in GS:
         for t in rng.standard_normal((50, G)).astype(np.float32):
             assert o32.entropy_alloc(t, G) == o32.entropy(t)
     w, x = workloads.generate(2, batch=2, seq=24)
@@ -458,6 +458,47 @@ def test_allocation_tile_must_align_with_quantization_tiles_and_divide_the_hidde
     assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=256)) == 0    # does not divide C
     assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=32)) == 0     # below G
     assert o32.packed_size(o32.make_cfg(1, 4, 384, 64, o32.F32, 3.5, alloc_tile=192)) > 0
+
+
+# ------------------- tiles of 8 and 16 channels, hidden sizes that are not powers of two
+
+@pytest.mark.parametrize("G,C_,dtype_name,low", [(8, 200, "f32", 3), (16, 208, "bf16", 3), (8, 64, "bf16", 2),
+                                                 (16, 1600, "f32", 2), (64, 1600, "bf16", 3), (32, 1600, "f32", 3)])
+def test_small_tiles_and_hidden_1600_streams_parse_and_decode_in_float64(G, C_, dtype_name, low):
+    # the tile-size ablation uses tiles of 8 channels; 1600 is a hidden size with 25 tiles of 64 per token
+    rng = np.random.default_rng(G + C_)
+    B, S = 2, 9
+    x = rng.standard_normal((B, S, C_)).astype(np.float32)
+    x[:, :, 5::37] *= 25.0
+    x[1, 2, :] = 0.0
+    dtype = o32.BF16 if dtype_name == "bf16" else o32.F32
+    xin = workloads.f32_to_bf16_bits(x) if dtype else x
+    budget = low + 0.3
+    cfg = o32.make_cfg(B, S, C_, G, dtype, budget, low_bits=low)
+    packed = o32.encode(cfg, xin)
+    T = o32.n_tiles(cfg)
+    k = o32.k_per_unit(cfg)
+    assert k == o64.k_per_unit(S * (C_ // G), np.float32(budget), low=low)     # the budget is an fp32 field
+    assert packed.size == o32.packed_size(cfg) == o64.section_offsets(T, G, B, k, low=low)["total"]
+    out64, s = o64.decode_stream(packed, T, G, B, k, low=low)
+    hdr = s["header"].view("<u4")
+    assert list(hdr[1:9]) == [1, dtype, B, S, C_, G, 0, k] and hdr[14] == G and hdr[15] == low
+    H, pivot, mn, mx = o32.tile_stats(cfg, xin)
+    xf = (workloads.bf16_bits_to_f32(xin) if dtype else x).reshape(T, G).astype(np.float64)
+    assert np.max(np.abs(H - o64.entropy(xf))) < 3e-5
+    assert np.array_equal(s["width"], o64.allocate(H, B, k, low=low))
+    assert np.array_equal(s["ranks"], s["rank_of"][::64])
+    assert np.array_equal(s["pivot"], pivot)
+    flag64, d64 = o64.outlier(xf)
+    assert np.array_equal(pivot & 0x7F, np.where(flag64, d64, 0)) and np.array_equal(pivot >> 7, flag64.astype(np.uint8))
+    sf = s["scale"].astype(np.float64); zf = s["zero"].astype(np.float64)
+    L = (1 << s["width"]) - 1
+    assert np.all(zf <= mn) and np.all(zf + L * sf >= mx) and np.all(s["codes"] <= L[:, None])
+    out32 = o32.decode(cfg, packed, o32.F32).reshape(T, G).astype(np.float64)
+    scale = np.maximum(np.abs(out64).max(axis=1, keepdims=True), 1e-30)
+    assert np.max(np.abs(out32 - out64) / scale) < 1e-5
+    err = np.linalg.norm(out64 - xf, axis=1)
+    assert np.all(err <= sf / 2 * math.sqrt(G) * (1 + 1e-3) + 1e-6 * np.abs(xf).max(axis=1))
 
 
 # ------------------------------------------- the INT2/INT3 mix (lo = 2)
@@ -558,7 +599,8 @@ def test_wire_cost_close_to_papers_4p41_bits():
 
 def test_invalid_configs_have_size_zero():
     assert o32.packed_size(o32.make_cfg(1, 4, 100, 64, o32.F32, 3.5)) == 0
-    assert o32.packed_size(o32.make_cfg(1, 4, 128, 16, o32.F32, 3.5)) == 0
+    assert o32.packed_size(o32.make_cfg(1, 4, 128, 4, o32.F32, 3.5)) == 0
+    assert o32.packed_size(o32.make_cfg(1, 4, 144, 48, o32.F32, 3.5)) == 0
     assert o32.packed_size(o32.make_cfg(1, 4, 128, 64, o32.F32, 4.5)) == 0
     assert o32.packed_size(o32.make_cfg(0, 4, 128, 64, o32.F32, 3.5)) == 0
 
