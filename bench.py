@@ -52,7 +52,7 @@ def cpu_baseline(index, w, alloc_tile, low_bits, budget):
     from oracle import o32
     batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
     ws, x = workloads.generate(index, batch=batch)
-    ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, ws.tile, ws.dtype, budget, alloc_tile=alloc_tile, low_bits=low_bits)
+    ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, w.tile, ws.dtype, budget, alloc_tile=alloc_tile, low_bits=low_bits)
     t0 = time.perf_counter()
     packed = o32.encode(ocfg, x)
     t1 = time.perf_counter()
@@ -158,6 +158,8 @@ def main():
     ap.add_argument("--alloc-tile", type=int, default=0,
                     help="allocation tile A in channels, a multiple of the tile width (default 0: A = G, the "
                          "metric's configuration)")
+    ap.add_argument("--tile", type=int, default=0, choices=(0, 8, 16, 32, 64, 128),
+                    help="quantization tile G (default 0: the workload's own)")
     ap.add_argument("--low-bits", type=int, default=0, choices=(0, 2, 3),
                     help="the two code widths are lo and lo+1 (default 0: 3, the metric's INT3/INT4)")
     ap.add_argument("--budget", type=float, default=None,
@@ -187,6 +189,9 @@ def main():
     tahq.binding._load()
 
     w, x = workloads.generate(args.config)
+    if args.tile:
+        import dataclasses
+        w = dataclasses.replace(w, tile=args.tile)
     budget = args.budget if args.budget is not None else w.budget_bits - (1.0 if args.low_bits == 2 else 0.0)
     cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, alloc_tile=args.alloc_tile,
                            low_bits=args.low_bits)
@@ -282,7 +287,7 @@ def main():
     dom_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
     # the stored counter readings belong to the metric's own configuration
-    stock = not wide and args.low_bits in (0, 3) and budget == w.budget_bits
+    stock = not wide and args.low_bits in (0, 3) and budget == w.budget_bits and not args.tile
     traffic = TRAFFIC_BYTES.get((w.name, dominant)) if stock else None
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -64,7 +64,7 @@ typedef enum {
     TAHQ_ERR_NULL = 1,                 /* a required pointer is NULL                     */
     TAHQ_ERR_INVALID_ARG = 2,          /* zero dimension, hidden % tile != 0, alloc_tile not a multiple of tile dividing hidden,
                                           budget outside [3,4] or NaN, bad enum */
-    TAHQ_ERR_UNSUPPORTED = 3,          /* tile not in {32, 64, 128}, or more than 2^31 tiles */
+    TAHQ_ERR_UNSUPPORTED = 3,          /* tile not in {8, 16, 32, 64, 128}, or more than 2^31 tiles */
     TAHQ_ERR_BUFFER_TOO_SMALL = 4,     /* packed capacity / packed_bytes below tahq_packed_size */
     TAHQ_ERR_WORKSPACE_TOO_SMALL = 5,  /* workspace capacity below tahq_workspace_size   */
     TAHQ_ERR_MISALIGNED = 6,           /* a device pointer is not 16-byte aligned        */
@@ -80,7 +80,7 @@ typedef struct {
     uint32_t batch;         /* B                                                                  */
     uint32_t seq;           /* S                                                                  */
     uint32_t hidden;        /* C; tensor is contiguous row-major [B, S, C]                        */
-    uint32_t tile;          /* G, the quantization tile: 32, 64 or 128                            */
+    uint32_t tile;          /* G, the quantization tile: 8, 16, 32, 64 (the paper's default) or 128 */
     uint32_t dtype;         /* tahq_dtype of the activation tensor                                */
     uint32_t scope;         /* 0 = rank the tiles of every sample (the paper); 1 = rank the whole tensor */
     float budget_bits;      /* mean payload bits per element, in [lo, lo+1] = [3.0, 4.0] by default */

@@ -31,7 +31,9 @@ inline uint32_t blocks_for(uint64_t threads) { return (uint32_t)((threads + 255)
 template <template <int, bool> class F, typename... Args>
 inline void dispatch(uint32_t G, bool bf16, Args... args)
 {
-    if (G == 32) { if (bf16) F<32, true>::run(args...); else F<32, false>::run(args...); }
+    if (G == 8) { if (bf16) F<8, true>::run(args...); else F<8, false>::run(args...); }
+    else if (G == 16) { if (bf16) F<16, true>::run(args...); else F<16, false>::run(args...); }
+    else if (G == 32) { if (bf16) F<32, true>::run(args...); else F<32, false>::run(args...); }
     else if (G == 64) { if (bf16) F<64, true>::run(args...); else F<64, false>::run(args...); }
     else { if (bf16) F<128, true>::run(args...); else F<128, false>::run(args...); }
 }

@@ -68,7 +68,7 @@ tahq_status make_shape(const tahq_config *c, Shape *s)
     if (c->dtype > TAHQ_BF16 || c->scope > 1) return TAHQ_ERR_INVALID_ARG;
     if (!(c->budget_bits >= (float)low && c->budget_bits <= (float)(low + 1u))) return TAHQ_ERR_INVALID_ARG;
     if (A % c->tile != 0 || c->hidden % A != 0) return TAHQ_ERR_INVALID_ARG;
-    if (c->tile != 32 && c->tile != 64 && c->tile != 128) return TAHQ_ERR_UNSUPPORTED;
+    if (c->tile != 8 && c->tile != 16 && c->tile != 32 && c->tile != 64 && c->tile != 128) return TAHQ_ERR_UNSUPPORTED;
     uint64_t M = c->hidden / c->tile;
     uint64_t T = (uint64_t)c->batch * c->seq * M;
     if (T >= (1ull << 31)) return TAHQ_ERR_UNSUPPORTED;
@@ -267,6 +267,8 @@ __device__ __forceinline__ void tile_butterfly(float *x, int t)
 }
 
 template <int G> struct TileConst;
+template <> struct TileConst<8>   { static constexpr float c = 0x1.6a09e6p-2f; };
+template <> struct TileConst<16>  { static constexpr float c = 0.25f; };
 template <> struct TileConst<32>  { static constexpr float c = 0x1.6a09e6p-3f; };
 template <> struct TileConst<64>  { static constexpr float c = 0.125f; };
 template <> struct TileConst<128> { static constexpr float c = 0x1.6a09e6p-4f; };

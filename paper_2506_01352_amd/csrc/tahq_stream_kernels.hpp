@@ -374,6 +374,8 @@ __global__ __launch_bounds__(256) void k_alloc_reduce(const float *__restrict__ 
 
 // Payload unit: a tile's payload is b units of G/8 bytes (b = 3 or 4).
 template <int G> struct Unit;
+template <> struct Unit<8>   { using type = uint8_t; };
+template <> struct Unit<16>  { using type = uint16_t; };
 template <> struct Unit<32>  { using type = uint32_t; };
 template <> struct Unit<64>  { using type = uint2; };
 template <> struct Unit<128> { using type = uint4; };
@@ -541,7 +543,14 @@ __device__ __forceinline__ void transform_row(const uint8_t *row, bool flag, flo
 template <int G, int W>
 __device__ __forceinline__ void pack_groups(const uint32_t *g4, uint32_t *dw)
 {
-    if constexpr (W == 4) {
+    if constexpr (G < 32) {
+        // at most 64 bits: two or four groups of 4 W bits through one 64-bit accumulator
+        uint64_t acc = 0;
+#pragma unroll
+        for (int g = 0; g < G / 4; ++g) acc |= (uint64_t)g4[g] << (4 * W * g);
+        dw[0] = (uint32_t)acc;
+        if constexpr (G == 16) dw[1] = (uint32_t)(acc >> 32);
+    } else if constexpr (W == 4) {
 #pragma unroll
         for (int i = 0; i < G / 8; ++i) dw[i] = g4[2 * i] | (g4[2 * i + 1] << 16);
     } else if constexpr (W == 3) {
@@ -622,7 +631,9 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
 #pragma unroll
     for (int u = 0; u < (int)WIDE; ++u) {
         if (u < LOW || b == WIDE) {
-            if constexpr (G == 32) dst[u] = dw[u];
+            if constexpr (G == 8) dst[u] = (uint8_t)(dw[0] >> (8 * u));
+            else if constexpr (G == 16) dst[u] = (uint16_t)(dw[u >> 1] >> (16 * (u & 1)));
+            else if constexpr (G == 32) dst[u] = dw[u];
             else if constexpr (G == 64) dst[u] = make_uint2(dw[2 * u], dw[2 * u + 1]);
             else dst[u] = make_uint4(dw[4 * u], dw[4 * u + 1], dw[4 * u + 2], dw[4 * u + 3]);
         }
@@ -782,7 +793,9 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
 #pragma unroll
     for (int u = 0; u < WIDE; ++u) {
         const U t = src[u];
-        if constexpr (G == 32) dw[u] = t;
+        if constexpr (G == 8) dw[0] |= (uint32_t)t << (8 * u);
+        else if constexpr (G == 16) dw[u >> 1] |= (uint32_t)t << (16 * (u & 1));
+        else if constexpr (G == 32) dw[u] = t;
         else if constexpr (G == 64) { dw[2 * u] = t.x; dw[2 * u + 1] = t.y; }
         else { dw[4 * u] = t.x; dw[4 * u + 1] = t.y; dw[4 * u + 2] = t.z; dw[4 * u + 3] = t.w; }
     }

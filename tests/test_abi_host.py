@@ -37,6 +37,9 @@ def test_sizes_match_the_oracle_layout_on_all_configs_and_variants():
     # allocation tiles of several quantization tiles, up to the whole token
     cases += [(3, 7, 96, 32, 0, 3.3, 0, 96, 0), (3, 7, 96, 32, 0, 3.3, 1, 32, 0), (2, 5, 640, 64, 1, 3.4, 0, 320, 0),
               (8, 4096, 8192, 64, 1, 3.25, 0, 8192, 0), (8, 4096, 8192, 64, 1, 3.25, 0, 128, 0)]
+    # tiles of 8 and 16 channels, a hidden size with 25 tiles of 64 per token
+    cases += [(3, 7, 96, 8, 0, 3.3, 0, 0, 0), (2, 5, 1600, 16, 1, 3.8, 0, 0, 0), (2, 5, 1600, 64, 1, 3.8, 0, 320, 0),
+              (8, 4096, 8192, 8, 1, 3.25, 0, 0, 0), (1, 3, 64, 8, 0, 2.5, 1, 32, 2)]
     # the INT2/INT3 mix
     cases += [(3, 7, 96, 32, 0, 2.3, 0, 0, 2), (8, 4096, 8192, 64, 1, 2.2, 0, 0, 2), (2, 5, 640, 64, 1, 3.0, 0, 320, 2),
               (2, 5, 640, 128, 1, 2.0, 1, 0, 2), (2, 5, 640, 64, 1, 3.4, 0, 0, 3)]
@@ -60,7 +63,7 @@ def test_defaults_and_version():
 
 def test_invalid_configs_are_rejected_with_size_zero():
     bad = [
-        dict(batch=0), dict(seq=0), dict(hidden=0), dict(hidden=100), dict(tile=16), dict(tile=48),
+        dict(batch=0), dict(seq=0), dict(hidden=0), dict(hidden=100), dict(tile=4), dict(tile=48), dict(tile=256),
         dict(budget_bits=2.9), dict(budget_bits=4.1), dict(budget_bits=float("nan")), dict(dtype=2), dict(scope=2),
         dict(alloc_tile=32), dict(alloc_tile=96), dict(alloc_tile=192), dict(alloc_tile=512),
         dict(low_bits=1), dict(low_bits=4), dict(low_bits=2), dict(low_bits=2, budget_bits=3.1),
@@ -108,7 +111,7 @@ def test_argument_errors_come_back_before_anything_is_enqueued():
     assert _call_encode(cfg, A, B_, size, W, ws - 1) == 5
     assert _call_encode(cfg, A + 4, B_, size, W, ws) == 6
     assert _call_encode(cfg, A, B_ + 8, size, W, ws) == 6
-    bad = tahq.make_config(2, 4, 256, 16, 0, 3.5)
+    bad = tahq.make_config(2, 4, 256, 4, 0, 3.5)
     assert _call_encode(bad, A, B_, 1 << 20, W, 1 << 20) == 3
     bad = tahq.make_config(2, 4, 250, 64, 0, 3.5)
     assert _call_encode(bad, A, B_, 1 << 20, W, 1 << 20) == 2

@@ -162,7 +162,7 @@ def test_output_dtype_other_than_input(tahq, index, shape):
     check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.5, out_dtype=other)
 
 
-@pytest.mark.parametrize("G", (32, 64, 128))
+@pytest.mark.parametrize("G", (8, 16, 32, 64, 128))
 @pytest.mark.parametrize("budget", (3.0, 3.5, 4.0))
 def test_edge_tiles(tahq, G, budget):
     tiles = workloads.edge_tiles(G)
@@ -236,7 +236,7 @@ def test_int2_int3_mix_bit_exact(tahq, index, shape, budget):
     check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, low_bits=2)
 
 
-@pytest.mark.parametrize("G", (32, 64, 128))
+@pytest.mark.parametrize("G", (8, 16, 32, 64, 128))
 def test_int2_int3_edge_tiles_other_output_type_and_allocation_tiles(tahq, G):
     tiles = workloads.edge_tiles(G)
     n = len(tiles) // 3 * 3
@@ -264,7 +264,7 @@ def test_massive_entropy_ties_are_broken_by_index(tahq):
 
 def test_single_tile_and_tiny_tensors(tahq):
     rng = np.random.default_rng(1)
-    for G in (32, 64, 128):
+    for G in (8, 16, 32, 64, 128):
         for B, S, M in ((1, 1, 1), (1, 1, 2), (2, 1, 1), (1, 5, 3)):
             x = rng.standard_normal((B, S, M * G)).astype(np.float32)
             x[..., 3] *= 25
@@ -378,7 +378,7 @@ def test_full_size_token_level_allocation_bit_exact(tahq):
 
 # ------------------------------------- every (tile width, dtype) pair, several batches and a ragged tail
 
-@pytest.mark.parametrize("G", (32, 64, 128))
+@pytest.mark.parametrize("G", (8, 16, 32, 64, 128))
 @pytest.mark.parametrize("dtype_name", ("f32", "bf16"))
 def test_all_tile_widths_and_dtypes_over_several_batches(tahq, G, dtype_name):
     # a workgroup handles min(256, 32768 / tile bytes) tiles: take 3 full batches plus a ragged tail, with
@@ -400,6 +400,23 @@ def test_all_tile_widths_and_dtypes_over_several_batches(tahq, G, dtype_name):
         check_case(tahq, xin, B, S, M * G, G, dtype, budget)
         check_case(tahq, xin, B, S, M * G, G, dtype, budget,
                    out_dtype=(tahq.BF16 if dtype == tahq.F32 else tahq.F32))
+
+
+@pytest.mark.parametrize("G", (8, 16, 32, 64))
+def test_hidden_size_1600_and_small_tiles_on_a_workload(tahq, G):
+    # 1600 channels: 200 / 100 / 50 / 25 tiles per token, sample boundaries inside batches and 64-tile groups
+    rng = np.random.default_rng(60 + G)
+    x = rng.standard_normal((3, 11, 1600)).astype(np.float32)
+    x[:, :, 7::53] *= 30.0
+    x[2, 4:6, :] = 0.0
+    for dtype, xin in ((tahq.F32, x), (tahq.BF16, workloads.f32_to_bf16_bits(x))):
+        _say(f"[case] hidden 1600 G={G} dtype={dtype}")
+        check_case(tahq, xin, 3, 11, 1600, G, dtype, 3.8)
+        check_case(tahq, xin, 3, 11, 1600, G, dtype, 2.2, low_bits=2)
+    check_case(tahq, x, 3, 11, 1600, G, tahq.F32, 3.4, alloc_tile=1600)
+    # configuration 4's tokens cut into tiles of G channels
+    w, y = workloads.generate(4, batch=2, seq=6)
+    check_case(tahq, y, w.batch, w.seq, w.hidden, G, w.dtype, w.budget_bits)
 
 
 def test_many_ranking_units_with_few_tiles_each(tahq):
