@@ -145,149 +145,13 @@ __device__ __forceinline__ float log_contract(float u)
     return __builtin_fmaf((float)e, kLn2, P);
 }
 
-__device__ __forceinline__ float tree8(const float *z)
-{
-    return ((z[0] + z[1]) + (z[2] + z[3])) + ((z[4] + z[5]) + (z[6] + z[7]));
-}
-
-__device__ __forceinline__ float xor_lane(float v, int m) { return __shfl_xor(v, m, 64); }
-__device__ __forceinline__ uint32_t xor_lane(uint32_t v, int m) { return (uint32_t)__shfl_xor((int)v, m, 64); }
-
-// Data-parallel-primitive move: every lane reads the lane that CTRL names (all lanes enabled).
-template <int CTRL>
-__device__ __forceinline__ float dpp(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
-constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;  // lane i <- lane 7-i  of its group of 8
-constexpr int kDppMirror = 0x140;      // lane i <- lane 15-i of its row of 16
-
-// Sum over the L lanes of a tile, continuing the adjacent-pair tree across lanes: pairs, quads,
-// then the two quads of an 8-group (mirror: by then the value is uniform inside a quad), then the
-// two halves of a 16-lane row.  Every lane ends with the same bits (a + b == b + a).
-template <int L>
-__device__ __forceinline__ float tile_sum(float s)
-{
-    s = s + dpp<kDppXor1>(s);
-    s = s + dpp<kDppXor2>(s);
-    if constexpr (L >= 8) s = s + dpp<kDppHalfMirror>(s);
-    if constexpr (L >= 16) s = s + dpp<kDppMirror>(s);
-    return s;
-}
-
-template <bool BF16>
-__device__ __forceinline__ void load8(const void *in, uint64_t elem, float *x)
-{
-    if constexpr (BF16) {
-        const uint4 w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(in) + elem);
-        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[2 * i] = __uint_as_float(ws[i] << 16);
-            x[2 * i + 1] = __uint_as_float(ws[i] & 0xffff0000u);
-        }
-    } else {
-        const float4 a = *reinterpret_cast<const float4 *>(static_cast<const float *>(in) + elem);
-        const float4 b = *reinterpret_cast<const float4 *>(static_cast<const float *>(in) + elem + 4);
-        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-    }
-}
-
-// fp32 -> bf16 bits, round to nearest even (finite values).
-__device__ __forceinline__ uint32_t bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-template <bool BF16>
-__device__ __forceinline__ void store8(void *out, uint64_t elem, const float *x)
-{
-    if constexpr (BF16) {
-        uint4 w;
-        w.x = bf16_rne(x[0]) | (bf16_rne(x[1]) << 16);
-        w.y = bf16_rne(x[2]) | (bf16_rne(x[3]) << 16);
-        w.z = bf16_rne(x[4]) | (bf16_rne(x[5]) << 16);
-        w.w = bf16_rne(x[6]) | (bf16_rne(x[7]) << 16);
-        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + elem) = w;
-    } else {
-        float *o = static_cast<float *>(out) + elem;
-        *reinterpret_cast<float4 *>(o) = make_float4(x[0], x[1], x[2], x[3]);
-        *reinterpret_cast<float4 *>(o + 4) = make_float4(x[4], x[5], x[6], x[7]);
-    }
-}
-
-// Eq. 1-2 for the tile spread over L lanes (8 raw elements per lane).
-template <int L>
-__device__ __forceinline__ float tile_entropy(const float *x, float eps_l1, float eps_log)
-{
-    float a[8], w[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a[i] = __builtin_fabsf(x[i]);
-    const float L1 = tile_sum<L>(tree8(a));
-    const float invL = 1.0f / (L1 + eps_l1);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float p = a[i] * invL;
-        const float u = p + eps_log;
-        w[i] = p * log_contract(u);
-    }
-    return 0.0f - tile_sum<L>(tree8(w));
-}
-
-// The unnormalised Sylvester butterfly over the tile: stages h = 1, 2, 4 inside the
-// lane, stages h = 8 .. G/2 between lanes t and t ^ (h/8).
-template <int L>
-__device__ __forceinline__ void tile_butterfly(float *x, int t)
-{
-#pragma unroll
-    for (int h = 1; h < 8; h <<= 1) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            if ((i & h) == 0) {
-                const float p = x[i], q = x[i + h];
-                x[i] = p + q;
-                x[i + h] = p - q;
-            }
-        }
-    }
-#pragma unroll
-    for (int m = 1; m < L; m <<= 1) {
-        const bool upper = (t & m) != 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float other = xor_lane(x[i], m);
-            x[i] = upper ? (other - x[i]) : (x[i] + other);
-        }
-    }
-}
-
+// fp32(1/sqrt(G)), the normalisation of Eq. 4.
 template <int G> struct TileConst;
 template <> struct TileConst<8>   { static constexpr float c = 0x1.6a09e6p-2f; };
 template <> struct TileConst<16>  { static constexpr float c = 0.25f; };
 template <> struct TileConst<32>  { static constexpr float c = 0x1.6a09e6p-3f; };
 template <> struct TileConst<64>  { static constexpr float c = 0.125f; };
 template <> struct TileConst<128> { static constexpr float c = 0x1.6a09e6p-4f; };
-
-// Swap coordinates 0 and d of the tile held by L lanes (P_d of Sec. 3.3).
-template <int L>
-__device__ __forceinline__ void tile_swap(float *x, int t, int lane_base, uint32_t d)
-{
-    const float v0 = __shfl(x[0], lane_base, 64);
-    float mine = x[0];
-#pragma unroll
-    for (int i = 1; i < 8; ++i) mine = ((d & 7u) == (uint32_t)i) ? x[i] : mine;
-    const float vd = __shfl(mine, lane_base + (int)(d >> 3), 64);
-    if (t == 0) x[0] = vd;
-    const bool holder = (uint32_t)t == (d >> 3);
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-        if (holder && (d & 7u) == (uint32_t)i) x[i] = v0;
-}
 
 // ---- binary16 metadata, rounded outwards ---------------------------------
 
