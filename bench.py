@@ -25,9 +25,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled by what
 # the same counter reads for a plain copy kernel of known size; see profiles/ for the summaries.
 TRAFFIC_BYTES = {
-    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_quant_pack"): int((264285.8 * 2.0 + 127357.4) * 1024),
-    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_entropy"): int((262223.7 * 2.0 + 16639.2) * 1024),
-    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_decode"): int((65621.1 * 2.0 + 524484.2) * 1024),
+    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_quant_pack"): int((264287.7 * 2.0 + 127357.4) * 1024),
+    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_entropy"): int((262221.1 * 2.0 + 16639.2) * 1024),
+    ("cfg4_bf16_8x4096x8192_g64_b3.25", "k_decode"): int((65614.1 * 2.0 + 524452.6) * 1024),
+    # the backward fixed-point compressor at its default 8 bits
+    ("cfg5_bf16_16x2048x5120_g32_b4.0", "k_naive_encode"): int((163871.6 * 2.0 + 166564.4) * 1024),
+    ("cfg5_bf16_16x2048x5120_g32_b4.0", "k_naive_decode"): int((83416.1 * 2.0 + 327685.7) * 1024),
 }
 
 
@@ -125,7 +128,9 @@ def naive_main(args):
                    "out_dtype": "same as input"},
         "kernel_ms": {"k_naive_encode": enc_ms, "k_naive_decode": dec_ms},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES.get((w.name, dominant)) if args.bits == 8 else None,
+                     "algorithmic_bytes_per_launch": alg,
                      "avg_launch_ms": dom_ms, "launches_timed": len(evs)},
     }
     if not args.no_cpu_baseline:
