@@ -3,12 +3,14 @@
 // Paper sections implemented by the kernels this file launches: Sec. 3.1 (tiles of G contiguous
 // channels), Sec. 3.2 Eq. 1-2 (entropy) and top-p% selection, Sec. 3.3 Eq. 3-4 (outlier test,
 // pivot swap, Hadamard transform, asymmetric quantizer), Sec. 3.4 (byte stream), Alg. 1 step 5
-// (dequantize).
+// (dequantize); and, for the backward direction, Sec. 3.5 / Alg. 1 steps 6-7 with the appendix's gradient
+// scaling (fixed-point compressor, tahq_naive_*).
 //
 // Numerics contract (identical results on any mapping of tiles to lanes):
 //   * all arithmetic is IEEE binary32, no contraction (-ffp-contract=off); fused multiply-adds
 //     only where written (__builtin_fmaf);
-//   * sums over a tile use the adjacent-pair binary tree;
+//   * sums over a tile use the adjacent-pair binary tree; an allocation tile of several quantization
+//     tiles adds their sums from left to right;
 //   * the Hadamard butterfly runs its stages h = 1, 2, ..., G/2 in that order;
 //   * log(u) = e*ln2 + P(m) with (m, e) = frexp(u) and a fixed degree-5 polynomial;
 //   * scale / zero-point are binary16, rounded outwards (up / down).
