@@ -148,7 +148,9 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in,
  *   packed_bytes                 bytes valid at d_packed (>= tahq_packed_size(cfg))
  *   d_out       device, written: B*S*C elements of out_dtype (fp32, or bf16 rounded to nearest even)
  *   d_workspace, workspace_capacity: reserved, not used; pass NULL and 0
- * The stream's header is not read back: cfg is trusted. */
+ * The stream's header is not read back: cfg is trusted.  The stream's contents are not: a
+ * stream damaged in transit decodes to meaningless values, but every address the decoder forms
+ * stays inside the stream and the output (the rank table is clamped, the pivot index masked). */
 tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t packed_bytes,
                         void *d_out, uint32_t out_dtype,
                         void *d_workspace, size_t workspace_capacity,

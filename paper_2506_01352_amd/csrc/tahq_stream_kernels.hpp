@@ -839,7 +839,7 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
         for (int c = 0; c < G / 4; ++c)
             *reinterpret_cast<float4 *>(row + c * 16) = make_float4(x[4 * c], x[4 * c + 1], x[4 * c + 2], x[4 * c + 3]);
     }
-    const uint32_t d = pv & 0x7fu;
+    const uint32_t d = pv & 0x7fu & (uint32_t)(G - 1);      // masked: a corrupted pivot byte stays inside the row
     if ((pv & 0x80u) && d != 0) {
         // undo P_d inside my row
         if constexpr (OUT_BF16) {
@@ -863,7 +863,7 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
 // The ragged last batch is handled after the loop by one workgroup.
 template <int G, bool OUT_BF16, int LOW>
 __global__ __launch_bounds__((Batch<G, OUT_BF16 ? 2 : 4>::TILES))
-void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout lay, uint32_t T, uint32_t total_four_bit)
+void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout lay, uint32_t T, uint32_t total_wide)
 {
     constexpr int ES = OUT_BF16 ? 2 : 4;
     using B = Batch<G, ES>;
@@ -893,8 +893,12 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap) + lane_zero;
 
     // 4-bit tiles before batch b (for the batch past the end of the tensor: all of them)
+    // The stream may have been damaged on its way here: the table's entries are clamped to the number of wide
+    // tiles the configuration implies, and a batch's count of wide tiles is taken as 0 if the table decreases, so
+    // that every payload address below stays inside the payload section whatever the stream holds.
     auto rank_of_batch = [&](uint64_t b) {
-        return b * B::TILES < T ? ranks[b * (B::TILES / 64)] : total_four_bit;
+        const uint32_t r = b * B::TILES < T ? ranks[b * (B::TILES / 64)] : total_wide;
+        return r < total_wide ? r : total_wide;
     };
     // slots 0..TILES of the window hold the entries of batches wfirst .. wfirst + TILES
     auto load_rank_window = [&](uint32_t wfirst) {
@@ -912,7 +916,8 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     auto fetch = [&](uint32_t batch) {
         const uint64_t j0 = (uint64_t)batch * B::TILES;
         m.rank0 = rank_lds[batch - wfirst];
-        const uint32_t total4 = rank_lds[batch - wfirst + 1] - m.rank0;
+        const uint32_t next_rank = rank_lds[batch - wfirst + 1];
+        const uint32_t total4 = next_rank > m.rank0 ? next_rank - m.rank0 : 0u;
         const uint64_t base = (uint64_t)LOW * j0 + m.rank0;
 #pragma unroll
         for (int i = 0; i < LOW; ++i) pre[i] = payload[base + (uint32_t)i * B::TILES + tid];
@@ -984,8 +989,11 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         load_meta<B::TILES>(packed, lay, j0, T, 0u, m);
         uint32_t b, rel, total4;
         tile_pos<B::TILES, LOW>(m, tid, &b, &rel, &total4);
-        const uint32_t span = (uint32_t)LOW * tail + total4;
-        const U *gsrc = payload + ((uint64_t)LOW * j0 + m.rank0);
+        // clamped like the table entries above: the span never reaches past the payload section
+        const uint32_t rank0 = m.rank0 < total_wide ? m.rank0 : total_wide;
+        const uint32_t room = total_wide - rank0;
+        const uint32_t span = (uint32_t)LOW * tail + (total4 < room ? total4 : room);
+        const U *gsrc = payload + ((uint64_t)LOW * j0 + rank0);
         for (uint32_t q = tid; q < span; q += B::TILES) pay[q] = gsrc[q];
         __syncthreads();
         if ((uint32_t)tid < tail)

@@ -466,3 +466,39 @@ def test_nan_inf_and_huge_inputs_are_lossy_but_never_a_fault(tahq):
         assert np.array_equal(packed[off2["payload"] + pay1: off2["total"]], want[off1["payload"]: off1["total"]])
         want_out = o32.decode(ocfg1, want, o32.F32)
         assert np.array_equal(out[n * G:].view(np.uint32), want_out.view(np.uint32))
+
+
+@pytest.mark.parametrize("G,low", [(64, 3), (32, 2), (8, 3), (128, 3), (16, 2)])
+def test_decoding_a_damaged_stream_stays_inside_its_buffers(tahq, G, low):
+    # The decoder clamps the rank table to the number of wide tiles the configuration implies, ignores a decreasing
+    # table, and masks the pivot index, so every address it forms lies inside the stream and the output whatever
+    # bytes arrive.  The values decoded from such a stream are meaningless; the buffers around them must be intact.
+    rng = np.random.default_rng(70 + G)
+    B, S, Cc = 2, 37, 5 * G * 3                       # several workgroups' batches and a ragged tail
+    cfg = tahq.make_config(B, S, Cc, G, tahq.BF16, low + 0.4, low_bits=low)
+    size = tahq.tahq_packed_size(cfg)
+    T = B * S * (Cc // G)
+    off = o64.section_offsets(T, G, B, tahq.tahq_k_per_unit(cfg), low)
+    streams = {"random bytes": rng.integers(0, 256, size=size, dtype=np.uint8)}
+    ones = np.full(size, 0xFF, np.uint8)
+    streams["all ones"] = ones
+    z = np.zeros(size, np.uint8)
+    z[off["ranks"]:off["pivot"]] = 0xFF               # a rank table far beyond the payload
+    z[off["bitmap"]:off["ranks"]] = 0xFF              # every tile claims to be wide
+    z[off["pivot"]:off["scale"]] = 0xFF               # every pivot index out of range
+    streams["hostile metadata"] = z
+    dec = rng.integers(0, 256, size=size, dtype=np.uint8)
+    table = dec[off["ranks"]:off["ranks"] + 4 * ((T + 63) // 64)].view("<u4")
+    table[:] = np.arange(table.size, 0, -1, dtype=np.uint32)          # a decreasing table
+    streams["decreasing rank table"] = dec
+    for name, host in streams.items():
+        for out_dtype in (tahq.F32, tahq.BF16):
+            _say(f"[case] damaged stream G={G} low={low}: {name}, out dtype {out_dtype}")
+            packed = Guarded(size)
+            packed.view.copy_(torch.from_numpy(host).cuda())
+            out = Guarded((4 if out_dtype == tahq.F32 else 2) * B * S * Cc)
+            tahq.tahq_decode(cfg, packed.view, out.view, out_dtype)
+            torch.cuda.synchronize()
+            out.check()
+            packed.check()
+            assert np.array_equal(packed.view.cpu().numpy(), host)     # the stream is only read
