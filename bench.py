@@ -34,6 +34,13 @@ TRAFFIC_BYTES = {
 }
 
 
+# HBM bytes of ALL kernels of one encode+decode step (same counters, same scaling), for the share of the HBM peak that
+# the whole path sustains: the three streaming kernels above plus prologue, two radix passes, segment counts, assignment.
+STEP_TRAFFIC_BYTES = {
+    "cfg4_bf16_8x4096x8192_g64_b3.25": 1975867392,
+}
+
+
 def algorithmic_bytes(w, packed_size, T, select):
     """Bytes each kernel must move per launch (per-element figures x elements of one launch)."""
     n, e = w.elements, w.bytes_per_element
@@ -310,6 +317,9 @@ def main():
                    "widths": [args.low_bits or 3, (args.low_bits or 3) + 1],
                    "out_dtype": "same as input"},
         "pct_hbm_peak_of_activation_rate": 100.0 * value / HBM_PEAK_GBS,
+        # measured HBM traffic of every kernel of the step (rocprofv3 counters, see profiles/) over the step's time
+        "pct_hbm_peak_of_measured_traffic": (100.0 * STEP_TRAFFIC_BYTES[w.name] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+                                             if stock and w.name in STEP_TRAFFIC_BYTES else None),
         "warmup_phase_ms": warm_ms,
         "roofline": roofline,
     }
