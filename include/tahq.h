@@ -12,6 +12,8 @@
  *     transform (1/sqrt(G)) H_G                               [Sec. 3.3, Eq. 4]
  *   - 3- or 4-bit width: the top-p% highest-entropy tiles of
  *     every sample get 4 bits, p = budget_bits - 3            [Sec. 3.2]
+ *     (lo and lo+1 bits with p = budget_bits - lo if low_bits
+ *     selects the INT2/INT3 mix of the appendix on bit allocation)
  *     (entropy and ranking may run on allocation tiles of
  *     A = alloc_tile channels, A a multiple of `tile`; the
  *     quantization tiles inside one share its width)
@@ -34,7 +36,7 @@
  *   - A failed launch is reported as TAHQ_ERR_HIP (hipGetLastError is consumed).
  *
  * Stream layout (little-endian; every section padded to 64 bytes), T = number
- * of tiles = batch*seq*hidden/tile, k = 4-bit allocation tiles per ranking unit:
+ * of tiles = batch*seq*hidden/tile, k = wide (lo+1 bit) allocation tiles per ranking unit:
  *   header   64 B   "TAHQ", version, dtype, batch, seq, hidden, tile, scope, k,
  *                   budget, tau, eps_l1, eps_log, eps_ratio, A, lo (32-bit words)
  *   bitmap   T bits         tile j -> byte j>>3, bit j&7; 1 = wide tile (lo+1 bits; 4 by default)
@@ -99,7 +101,8 @@ typedef struct {
  * dtype bf16, dimensions 0).  cfg: host, written.  No error: NULL is ignored. */
 void tahq_config_default(tahq_config *cfg);
 
-/* Number of 4-bit allocation tiles per ranking unit: round((budget_bits - 3) * n) with n
+/* Number of wide (lo+1 bit, 4-bit by default) allocation tiles per ranking unit:
+ * round((budget_bits - lo) * n) with n
  * the allocation tiles of one sample (scope 0) or of the tensor (scope 1)  [Sec. 3.2, top-p%].
  * Returns 0 for an invalid cfg (a valid cfg with budget 3.0 also gives 0). */
 uint64_t tahq_k_per_unit(const tahq_config *cfg);

@@ -1,5 +1,5 @@
-// Top-p% tile selection (Sec. 3.2): inside every ranking unit the k tiles of highest entropy get
-// 4 bits, ties going to the lower tile index.  Exact, deterministic, no sort:
+// Top-p% tile selection (Sec. 3.2): inside every ranking unit the k (allocation) tiles of highest entropy get
+// the wider code (4 bits by default), ties going to the lower tile index.  Exact, deterministic, no sort:
 //
 //   * entropies map to order-preserving 32-bit keys;
 //   * three histogram passes (10 + 11 + 11 bits, from the top; the first one is normally folded into
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, 
 // boundaries (otherwise one byte per tile goes to `sel_bytes` and k_bitmap_pack follows).
 // A block owns 4 consecutive segments.  Its first wavefront sums the segment counts that precede
 // the block: equal keys before it (they are taken in index order until `take` are used up) and
-// 4-bit tiles before it (every earlier ranking unit contributes exactly k).
+// wide tiles before it (every earlier ranking unit contributes exactly k).
 __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uint32_t n, uint32_t k, uint32_t nseg,
                                                 const uint32_t *__restrict__ state,
                                                 const uint32_t *__restrict__ seg,
@@ -350,10 +350,10 @@ __global__ __launch_bounds__(256) void k_bitmap_pack(const uint8_t *__restrict__
 }
 
 // Allocation tiles of m > 1 quantization tiles (Sec. 3.2): the selection ran over allocation tiles and left
-// one byte per allocation tile in `sel_a` and, in `ranks_a`, the 4-bit allocation tiles before each group of
+// one byte per allocation tile in `sel_a` and, in `ranks_a`, the wide allocation tiles before each group of
 // 64.  This kernel writes the stream's bit map and rank table over QUANTIZATION tiles: tile j takes the
-// width of allocation tile j / m, and the 4-bit quantization tiles before j are m times the 4-bit
-// allocation tiles before j / m, plus j % m if its own allocation tile has 4 bits.  One wavefront per
+// width of allocation tile j / m, and the wide quantization tiles before j are m times the wide
+// allocation tiles before j / m, plus j % m if its own allocation tile is wide.  One wavefront per
 // 64 quantization tiles.
 __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict__ sel_a,
                                                       const uint32_t *__restrict__ ranks_a, uint32_t T, uint32_t m,

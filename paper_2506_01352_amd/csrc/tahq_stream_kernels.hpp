@@ -647,9 +647,9 @@ template <int G, int ESIZE>
 struct QuantPackOccupancy { static constexpr int WAVES_PER_SIMD = (G * ESIZE <= 128) ? 4 : 1; };
 
 // One workgroup per batch of TILES tiles, in two rounds.  Round 1: lane i examines tile i (Eq. 3, pivot
-// swap in LDS).  The tiles are then regrouped by class -- (plain | transformed) x (3 | 4 bit) -- so that in
+// swap in LDS).  The tiles are then regrouped by class -- (plain | transformed) x (narrow | wide) -- so that in
 // round 2, where lane p takes the p-th tile in class order, most wavefronts hold a single class: the
-// Hadamard butterfly runs only in the wavefronts that hold transformed tiles, and the 3-/4-bit packing
+// Hadamard butterfly runs only in the wavefronts that hold transformed tiles, and the two packing
 // paths rarely both run.  The payload buffer reuses the rows' LDS once every lane holds its tile in
 // registers, which keeps the workgroup small enough for four to share a compute unit: this kernel
 // lives on the loads of its neighbours being in flight while it computes.
@@ -892,7 +892,7 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     asm volatile("" : "+v"(lane_zero));
     const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap) + lane_zero;
 
-    // 4-bit tiles before batch b (for the batch past the end of the tensor: all of them)
+    // wide tiles before batch b (for the batch past the end of the tensor: all of them)
     // The stream may have been damaged on its way here: the table's entries are clamped to the number of wide
     // tiles the configuration implies, and a batch's count of wide tiles is taken as 0 if the table decreases, so
     // that every payload address below stays inside the payload section whatever the stream holds.
@@ -939,7 +939,7 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         tile_pos<B::TILES, LOW>(m, tid, &b, &rel, &total4);
 #pragma unroll
         for (int i = 0; i < (int)WIDE; ++i) pay[(uint32_t)i * B::TILES + tid] = pre[i];
-        // Tiles are regrouped by class -- (plain | transformed) x (3 | 4 bit) -- as in the encoder: lane p decodes
+        // Tiles are regrouped by class -- (plain | transformed) x (narrow | wide) -- as in the encoder: lane p decodes
         // the p-th tile in class order, so the butterfly runs only in the wavefronts that hold transformed tiles.
         tile_meta[tid] = make_uint2(s16 | (z16 << 16), pv | ((b == WIDE) ? 0x100u : 0u) | (rel << 9));
         const uint32_t cls = ((pv >> 7) << 1) | (b == WIDE ? 1u : 0u);
