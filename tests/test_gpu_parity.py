@@ -355,6 +355,23 @@ def test_full_size_int2_int3_mix_bit_exact(tahq):
     assert np.array_equal(got, want_out)
 
 
+@pytest.mark.parametrize("G", (8, 16))
+def test_one_full_sample_in_small_tiles_bit_exact(tahq, G):
+    # one sample of the headline tensor cut into tiles of 8 / 16 channels: 4.2 M / 2.1 M tiles, thousands of batches
+    w, x = workloads.generate(4, batch=1)
+    _say(f"[case] {w.name} one sample, G={G}")
+    cfg = tahq.make_config(1, w.seq, w.hidden, G, w.dtype, w.budget_bits)
+    ocfg = o32.make_cfg(1, w.seq, w.hidden, G, w.dtype, w.budget_bits)
+    codec = tahq.Codec(cfg)
+    codec.encode(to_device(x))
+    codec.decode()
+    torch.cuda.synchronize()
+    want = o32.encode(ocfg, x)
+    compare_streams(codec.packed.cpu().numpy(), want, x.size // G, G, 1, o32.k_per_unit(ocfg))
+    got = codec.out.cpu().view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, o32.decode(ocfg, want, w.dtype))
+
+
 def test_full_size_token_level_allocation_bit_exact(tahq):
     # the headline tensor with A = C (Sec. 3.2's token-level special case) and with A = 2G
     w, x = workloads.generate(4)
