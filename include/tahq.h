@@ -132,7 +132,12 @@ enum {
     TAHQ_PHASE_ENTROPY = 2,    /* Eq. 1-2 for every tile (skipped when budget is 3.0 or 4.0)  */
     TAHQ_PHASE_SELECT = 4,     /* top-p% selection: bit map and rank table     [Sec. 3.2]     */
     TAHQ_PHASE_QUANT = 8,      /* Eq. 3-4, quantize, pack                      [Sec. 3.3-3.4] */
-    TAHQ_PHASE_ALL = 15
+    TAHQ_PHASE_ALL = 15,
+    /* Not a phase but an option, OR-ed into `phases`: rank even small ranking units (up to 65536
+     * tiles, which one workgroup ranks in a single launch by default) with the general multi-launch
+     * selection.  Same result; meant for tests and timing.  Pass it with every phase of a call
+     * sequence, since the prologue and the entropy phase prepare different scratch for the two. */
+    TAHQ_SELECT_MULTI_LAUNCH = 16
 };
 
 /* tahq_encode split by phase, so that a caller can put its own events between the
@@ -140,7 +145,7 @@ enum {
  * `phases` is an OR of TAHQ_PHASE_*; a phase needs the results of the earlier ones, left
  * in d_packed / d_workspace by previous calls with the same cfg and buffers.  Calling it
  * once per phase, in order, on one stream equals tahq_encode.  Other arguments and
- * errors as tahq_encode; phases == 0 or unknown bits give TAHQ_ERR_INVALID_ARG. */
+ * errors as tahq_encode; no phase bit or unknown bits give TAHQ_ERR_INVALID_ARG. */
 tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in,
                                void *d_packed, size_t packed_capacity,
                                void *d_workspace, size_t workspace_capacity,

@@ -159,6 +159,7 @@ def tahq_encode(cfg, d_in, d_packed, d_workspace, stream=None, packed_capacity=N
 
 
 PHASE_PROLOGUE, PHASE_ENTROPY, PHASE_SELECT, PHASE_QUANT, PHASE_ALL = 1, 2, 4, 8, 15
+SELECT_MULTI_LAUNCH = 16      # option bit for tahq_encode_phases: see include/tahq.h
 
 
 def tahq_encode_phases(cfg, d_in, d_packed, d_workspace, phases, stream=None):

@@ -280,6 +280,8 @@ tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, fl
 tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d_packed, size_t packed_capacity,
                                void *d_workspace, size_t workspace_capacity, uint32_t phases, tahq_stream stream)
 {
+    const bool multi_launch = (phases & TAHQ_SELECT_MULTI_LAUNCH) != 0;
+    phases &= ~(uint32_t)TAHQ_SELECT_MULTI_LAUNCH;
     if (phases == 0 || (phases & ~(uint32_t)TAHQ_PHASE_ALL)) return TAHQ_ERR_INVALID_ARG;
     Shape s;
     tahq_status rc = make_shape(cfg, &s);
@@ -300,6 +302,8 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     uint32_t *ranks = reinterpret_cast<uint32_t *>(packed + lay.ranks);
     const bool select = s.kA != 0 && s.kA != s.nA;
     const bool wide = s.m > 1;     // allocation tiles of several quantization tiles
+    // ranking units that one workgroup can hold are ranked in a single launch
+    const bool small_units = select && s.nA <= kSmallUnitMaxKeys && !multi_launch;
 
     // header, section padding, selection scratch
     HeaderWords hdr;
@@ -321,9 +325,10 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
                                    lay.scale + 2 * s.T, lay.zero + 2 * s.T};
     const uint64_t sec_end[5] = {lay.ranks, lay.pivot, lay.scale, lay.zero, lay.payload};
     for (int i = 0; i < 5; ++i) { pads.begin[i] = sec_begin[i]; pads.len[i] = (uint32_t)(sec_end[i] - sec_begin[i]); }
-    const uint32_t zero_words = select ? (uint32_t)(ws.zero_bytes / 4) : 0u;
+    const bool histograms = select && !small_units;
+    const uint32_t zero_words = histograms ? (uint32_t)(ws.zero_bytes / 4) : 0u;
     if (phases & TAHQ_PHASE_PROLOGUE)
-        hipLaunchKernelGGL(k_prologue, dim3(select ? 32 : 1), dim3(256), 0, st, packed, hdr, pads,
+        hipLaunchKernelGGL(k_prologue, dim3(histograms ? 32 : 1), dim3(256), 0, st, packed, hdr, pads,
                            reinterpret_cast<uint32_t *>(wsb + ws.hist0), zero_words);
 
     if (select) {
@@ -336,16 +341,34 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
         uint8_t *sel = wsb + ws.sel;
         // the entropy kernel builds the first-digit histogram itself when units are whole batches
         bool fused = false;
-        if (!wide) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
+        if (!wide && !small_units) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
         if (phases & TAHQ_PHASE_ENTROPY) {
             if (wide)
                 dispatch<LaunchAllocEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, H, reinterpret_cast<float *>(wsb + ws.part),
                                              reinterpret_cast<float *>(wsb + ws.inv_norm), (uint32_t)s.T, s.m,
                                              cfg->eps_l1, cfg->eps_log, st);
             else
-                launch_entropy(s, cfg, d_in, H, hist0, st);
+                launch_entropy(s, cfg, d_in, H, small_units ? (uint32_t *)nullptr : hist0, st);
         }
-        if (phases & TAHQ_PHASE_SELECT) {
+        if ((phases & TAHQ_PHASE_SELECT) && small_units) {
+            const uint32_t n32 = (uint32_t)s.nA, k32 = (uint32_t)s.kA;
+            const int aligned = (!wide && s.n % 64 == 0) ? 1 : 0;
+            uint32_t *ranks_a = reinterpret_cast<uint32_t *>(wsb + ws.ranks_a);
+            uint32_t *rank_out = wide ? ranks_a : ranks;
+            const dim3 grid(s.U), block(kSmallUnitThreads);
+            if (n32 <= 16 * kSmallUnitThreads)
+                hipLaunchKernelGGL((k_select_small<16>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
+            else if (n32 <= 32 * kSmallUnitThreads)
+                hipLaunchKernelGGL((k_select_small<32>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
+            else
+                hipLaunchKernelGGL((k_select_small<64>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
+            if (wide)
+                hipLaunchKernelGGL(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                                   (const uint8_t *)sel, (const uint32_t *)ranks_a, (uint32_t)s.T, s.m, bitmap, ranks);
+            else if (!aligned)
+                hipLaunchKernelGGL(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                                   (const uint8_t *)sel, (uint32_t)s.T, bitmap);
+        } else if (phases & TAHQ_PHASE_SELECT) {
             // the selection ranks allocation tiles; with A = G they are the stream's tiles
             const uint32_t n32 = (uint32_t)s.nA, k32 = (uint32_t)s.kA;
             const dim3 rgrid(ws.hb, s.U);

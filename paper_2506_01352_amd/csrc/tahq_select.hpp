@@ -375,6 +375,138 @@ __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict_
     }
 }
 
+// ---- small ranking units: the whole selection in one launch
+
+constexpr uint32_t kSmallUnitThreads = 1024;
+constexpr uint32_t kSmallUnitMaxKeys = 65536;    // 64 keys per thread
+
+// A ranking unit of at most 1024 * KPT keys, ranked by ONE workgroup that keeps the keys in registers: the
+// three radix passes run on an LDS histogram, the per-group counts and their prefix sums stay in LDS, and
+// the bit map and rank table (or, for units that do not start on 64-tile boundaries, one byte per tile and
+// the rank entries of the 64-tile groups) are written at the end.  Same result as k_radix_pass x 3,
+// k_seg_count and k_assign, in one launch instead of five: small tensors are bound by launch latency.
+// Thread (wave w, lane l) holds, for r = 0 .. KPT-1, the key of tile 64 * (16 r + w) + l of the unit.
+template <int KPT>
+__global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float *__restrict__ H, uint32_t n, uint32_t k,
+                                                                    uint64_t *__restrict__ bitmap,
+                                                                    uint32_t *__restrict__ ranks,
+                                                                    uint8_t *__restrict__ sel_bytes, int aligned)
+{
+    constexpr int NG = 16 * KPT;                 // 64-tile groups the workgroup can hold
+    // Digits of 8, 12 and 12 bits from the top.  The histogram keeps several copies of every bin, indexed by
+    // the low bits of the lane: a wavefront's atomics on one LDS address are serialized, and the first digit
+    // (sign and most of the exponent) takes one or two values, as does any digit under massive ties.
+    // 32 copies of 256 bins, or 2 copies of 4096 bins.
+    constexpr int kBins = 4096;
+    __shared__ uint32_t copies[8192];
+    __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t chosen[2];
+    __shared__ uint32_t grp_eq[NG], grp_sel[NG];
+    const uint32_t u = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *uH = H + (uint64_t)u * n;
+    const uint64_t below = (1ull << lane) - 1ull;
+
+    uint32_t key[KPT];
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+        const uint32_t i = (uint32_t)(16 * r + wave) * 64u + lane;
+        key[r] = i < n ? order_key(uH[i]) : 0u;
+    }
+    auto in_unit = [&](int r) { return (uint32_t)(16 * r + wave) * 64u + lane < n; };
+
+    uint32_t want = k, hi = 0;
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 24 : (pass == 1 ? 12 : 0);
+        const uint32_t mask = pass == 0 ? 255u : 4095u;
+        const int hi_shift = pass == 1 ? 24 : 12;
+        const int copy_bits = pass == 0 ? 5 : 1;
+        const uint32_t my_copy = (uint32_t)lane & ((1u << copy_bits) - 1u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copies[i * (int)kSmallUnitThreads + tid] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const bool active = in_unit(r) && (pass == 0 || (key[r] >> hi_shift) == hi);
+            if (active) atomicAdd(&copies[((((key[r] >> shift) & mask)) << copy_bits) | my_copy], 1u);
+        }
+        __syncthreads();
+        // thread t adds up the copies of bins t, t + 1024, ... (a 256-bin digit leaves the rest empty)
+#pragma unroll
+        for (int part = 0; part < kBins / (int)kSmallUnitThreads; ++part) {
+            const uint32_t bin = (uint32_t)tid + kSmallUnitThreads * part;
+            uint32_t sum = 0;
+            if (bin <= mask) {
+                for (int c = 0; c < (1 << copy_bits); ++c) sum += copies[(bin << copy_bits) + c];
+            }
+            lh[bin] = sum;
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t bin, rem;
+            pick_bin<kBins>(lh, want, &bin, &rem);
+            if (lane == 0) { chosen[0] = bin; chosen[1] = rem; }
+        }
+        __syncthreads();
+        hi = pass == 0 ? chosen[0] : ((hi << 12) | chosen[0]);
+        want = chosen[1];
+    }
+    const uint32_t thr = hi, take = want;        // the k-th largest key, and how many tiles equal to it are taken
+
+    // per 64-tile group: keys equal to thr, keys above it
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+        const bool ok = in_unit(r);
+        const uint64_t eqm = __ballot(ok && key[r] == thr);
+        const uint64_t gtm = __ballot(ok && key[r] > thr);
+        if (lane == 0) {
+            grp_eq[16 * r + wave] = (uint32_t)__popcll(eqm);
+            grp_sel[16 * r + wave] = (uint32_t)__popcll(gtm);
+        }
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // lane l owns the PER consecutive groups PER*l ..: equal keys before each group (they are taken in index
+        // order until `take` are used up), then wide tiles before each group
+        constexpr int PER = NG / 64;
+        uint32_t e[PER], c[PER], esum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { e[i] = grp_eq[lane * PER + i]; esum += e[i]; }
+        uint32_t eq_before = wave_incl_scan(esum) - esum;
+        uint32_t csum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const uint32_t left = eq_before < take ? take - eq_before : 0u;
+            c[i] = grp_sel[lane * PER + i] + (e[i] < left ? e[i] : left);
+            grp_eq[lane * PER + i] = eq_before;
+            eq_before += e[i];
+            csum += c[i];
+        }
+        uint32_t rank_before = wave_incl_scan(csum) - csum;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { grp_sel[lane * PER + i] = rank_before; rank_before += c[i]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+        const uint32_t g = (uint32_t)(16 * r + wave);
+        const bool ok = in_unit(r);
+        const bool eq = ok && key[r] == thr;
+        const uint64_t eqm = __ballot(eq);
+        const bool sel = ok && (key[r] > thr || (eq && grp_eq[g] + (uint32_t)__popcll(eqm & below) < take));
+        const uint64_t selm = __ballot(sel);
+        const uint64_t jg = (uint64_t)u * n + (uint64_t)g * 64u + lane;     // tile index in the tensor
+        const uint32_t rank = u * k + grp_sel[g];
+        if (aligned) {
+            if (lane == 0 && ok) { bitmap[jg >> 6] = selm; ranks[jg >> 6] = rank; }
+        } else if (ok) {
+            sel_bytes[jg] = sel ? 1 : 0;
+            if ((jg & 63u) == 0) ranks[jg >> 6] = rank + (uint32_t)__popcll(selm & below);
+        }
+    }
+}
+
 // Budget 3.0 or 4.0: every tile has the same width.
 __global__ __launch_bounds__(256) void k_bitmap_const(uint32_t T, int all4, uint64_t *__restrict__ bitmap,
                                                       uint32_t *__restrict__ ranks)

@@ -71,9 +71,15 @@ def run_gpu(tahq, cfg, x, out_dtype, want_alloc_entropy=False):
     ws.view.fill_(0x3C)         # the encoder must not rely on what the call above left behind
     tahq.tahq_encode(cfg, d_in, packed.view, ws.view)
     tahq.tahq_decode(cfg, packed.view, out.view, out_dtype)
+    # the same encode with the general multi-launch selection (small ranking units take a single-launch path
+    # by default): byte-identical stream
+    packed2 = Guarded(tahq.tahq_packed_size(cfg))
+    ws.view.fill_(0xC3)
+    tahq.tahq_encode_phases(cfg, d_in, packed2.view, ws.view, tahq.PHASE_ALL | tahq.SELECT_MULTI_LAUNCH)
     torch.cuda.synchronize()
-    for g in (packed, ws, ent, ent_a, out):
+    for g in (packed, packed2, ws, ent, ent_a, out):
         g.check()
+    assert torch.equal(packed.view, packed2.view), "single-launch and multi-launch selection disagree"
     H = ent.view.cpu().numpy().view(np.float32)
     o = out.view.cpu().numpy().view(np.float32 if out_dtype == tahq.F32 else np.uint16)
     if want_alloc_entropy:
@@ -434,6 +440,22 @@ def test_hidden_size_1600_and_small_tiles_on_a_workload(tahq, G):
     # configuration 4's tokens cut into tiles of G channels
     w, y = workloads.generate(4, batch=2, seq=6)
     check_case(tahq, y, w.batch, w.seq, w.hidden, G, w.dtype, w.budget_bits)
+
+
+@pytest.mark.parametrize("B,S,Cc,G", [(1, 1000, 1600, 64), (2, 1024, 1024, 32), (1, 700, 4096, 64), (1, 513, 2048, 32),
+                                       (3, 1024, 1024, 64), (2, 260, 8064, 64)])
+def test_ranking_units_of_every_single_launch_size(tahq, B, S, Cc, G):
+    # units of 25000 / 32768 / 44800 / 32832 / 16384 / 32760 tiles: every keys-per-thread variant of the single-launch
+    # selection, aligned and not aligned to 64 tiles, with all-zero tokens (massive ties) and near-constant tokens
+    rng = np.random.default_rng(B * S + Cc + G)
+    x = rng.standard_normal((B, S, Cc)).astype(np.float32)
+    x[:, :, 3::97] *= 20.0
+    x[:, ::9, :] = 0.0                                   # ties at entropy 0
+    x[:, 1::13, :] = 1.5                                 # ties at entropy ln G
+    _say(f"[case] single-launch selection: units of {S * (Cc // G)} tiles, {B}x{S}x{Cc} G={G}")
+    for budget in (3.07, 3.5, 3.93):
+        check_case(tahq, workloads.f32_to_bf16_bits(x), B, S, Cc, G, tahq.BF16, budget)
+    check_case(tahq, x, B, S, Cc, G, tahq.F32, 3.3, scope=1 if B * S * (Cc // G) <= 65536 else 0)
 
 
 def test_many_ranking_units_with_few_tiles_each(tahq):
