@@ -400,6 +400,7 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     constexpr int kBins = 4096;
     __shared__ uint32_t copies[8192];
     __shared__ uint32_t lh[kBins];
+    __shared__ uint32_t chunk_sum[kBins / 64];   // totals of 64 consecutive bins
     __shared__ uint32_t chosen[2];
     __shared__ uint32_t grp_eq[NG], grp_sel[NG];
     const uint32_t u = blockIdx.x;
@@ -443,10 +444,29 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
             lh[bin] = sum;
         }
         __syncthreads();
+        // the bin that holds the want-th largest key, in two levels with unit-stride LDS reads: totals of chunks
+        // of 64 bins (four chunks per wavefront), then the chunk from the top, then the bin inside it
+#pragma unroll
+        for (int c = 0; c < kBins / 64 / 16; ++c) {
+            const int chunk = wave * (kBins / 64 / 16) + c;
+            uint32_t v = lh[chunk * 64 + lane];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += (uint32_t)__shfl_xor((int)v, off, 64);
+            if (lane == 0) chunk_sum[chunk] = v;
+        }
+        __syncthreads();
         if (tid < 64) {
-            uint32_t bin, rem;
-            pick_bin<kBins>(lh, want, &bin, &rem);
-            if (lane == 0) { chosen[0] = bin; chosen[1] = rem; }
+            const uint32_t cs = chunk_sum[63 - lane];                       // lane l: chunk 63 - l, from the top
+            const uint32_t above = wave_incl_scan(cs) - cs;
+            const uint64_t who = __ballot(above < want && want <= above + cs);
+            const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
+            const uint32_t chunk = 63u - (uint32_t)src;
+            const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
+            const uint32_t bs = lh[chunk * 64 + (63 - lane)];               // lane l: bin 63 - l of the chunk
+            const uint32_t above2 = wave_incl_scan(bs) - bs;
+            const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
+            const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
+            if (lane == src2) { chosen[0] = chunk * 64 + (63u - (uint32_t)src2); chosen[1] = want2 - above2; }
         }
         __syncthreads();
         hi = pass == 0 ? chosen[0] : ((hi << 12) | chosen[0]);
