@@ -22,15 +22,22 @@
 
 namespace tahq {
 
-// Inclusive scan over the 64 lanes of a wavefront.
+// Inclusive scan over the 64 lanes of a wavefront with data-parallel-primitive moves (all lanes must be
+// enabled): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 / 2 is added to
+// row 1 / 3, then the last lane of the lower half to the upper half.  A lane without a source adds 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
 {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_up((int)v, off, 64);
-        if (lane >= off) v += o;
-    }
+    v += dpp_or_zero<0x111, 0xF>(v);     // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);     // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);     // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);     // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);     // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xC>(v);     // row_bcast:31 into rows 2 and 3
     return v;
 }
 
@@ -399,8 +406,8 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     // 32 copies of 256 bins, or 2 copies of 4096 bins.
     constexpr int kBins = 4096;
     __shared__ uint32_t copies[8192];
-    __shared__ uint32_t lh[kBins];
-    __shared__ uint32_t chunk_sum[kBins / 64];   // totals of 64 consecutive bins
+    __shared__ uint32_t lh[kBins + kBins / 64];  // bin b at b + b/64: a lane that walks one chunk of 64 bins while
+                                                 // its neighbours walk theirs meets no bank conflict
     __shared__ uint32_t chosen[2];
     __shared__ uint32_t grp_eq[NG], grp_sel[NG];
     const uint32_t u = blockIdx.x;
@@ -441,28 +448,21 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
             if (bin <= mask) {
                 for (int c = 0; c < (1 << copy_bits); ++c) sum += copies[(bin << copy_bits) + c];
             }
-            lh[bin] = sum;
+            lh[bin + (bin >> 6)] = sum;
         }
         __syncthreads();
-        // the bin that holds the want-th largest key, in two levels with unit-stride LDS reads: totals of chunks
-        // of 64 bins (four chunks per wavefront), then the chunk from the top, then the bin inside it
-#pragma unroll
-        for (int c = 0; c < kBins / 64 / 16; ++c) {
-            const int chunk = wave * (kBins / 64 / 16) + c;
-            uint32_t v = lh[chunk * 64 + lane];
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) v += (uint32_t)__shfl_xor((int)v, off, 64);
-            if (lane == 0) chunk_sum[chunk] = v;
-        }
-        __syncthreads();
+        // the bin that holds the want-th largest key, in two levels: the total of each chunk of 64 bins, the
+        // chunk from the top, then the bin inside it
         if (tid < 64) {
-            const uint32_t cs = chunk_sum[63 - lane];                       // lane l: chunk 63 - l, from the top
+            uint32_t cs = 0;                                                // lane l: chunk 63 - l, from the top
+#pragma unroll 16
+            for (int i = 0; i < 64; ++i) cs += lh[(63 - lane) * 65 + i];
             const uint32_t above = wave_incl_scan(cs) - cs;
             const uint64_t who = __ballot(above < want && want <= above + cs);
             const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
             const uint32_t chunk = 63u - (uint32_t)src;
             const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
-            const uint32_t bs = lh[chunk * 64 + (63 - lane)];               // lane l: bin 63 - l of the chunk
+            const uint32_t bs = lh[chunk * 65 + (63 - lane)];               // lane l: bin 63 - l of the chunk
             const uint32_t above2 = wave_incl_scan(bs) - bs;
             const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
             const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
