@@ -133,7 +133,7 @@ enum {
     TAHQ_PHASE_SELECT = 4,     /* top-p% selection: bit map and rank table     [Sec. 3.2]     */
     TAHQ_PHASE_QUANT = 8,      /* Eq. 3-4, quantize, pack                      [Sec. 3.3-3.4] */
     TAHQ_PHASE_ALL = 15,
-    /* Not a phase but an option, OR-ed into `phases`: rank even small ranking units (up to 65536
+    /* Not a phase but an option, OR-ed into `phases`: rank even small ranking units (up to 32768
      * tiles, which one workgroup ranks in a single launch by default) with the general multi-launch
      * selection.  Same result; meant for tests and timing.  Pass it with every phase of a call
      * sequence, since the prologue and the entropy phase prepare different scratch for the two. */

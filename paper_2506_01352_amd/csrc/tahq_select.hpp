@@ -385,7 +385,7 @@ __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict_
 // ---- small ranking units: the whole selection in one launch
 
 constexpr uint32_t kSmallUnitThreads = 1024;
-constexpr uint32_t kSmallUnitMaxKeys = 65536;    // 64 keys per thread
+constexpr uint32_t kSmallUnitMaxKeys = 32768;    // 32 keys per thread (beyond that the multi-launch selection is faster)
 
 // A ranking unit of at most 1024 * KPT keys, ranked by ONE workgroup that keeps the keys in registers: the
 // three radix passes run on an LDS histogram, the per-group counts and their prefix sums stay in LDS, and
