@@ -646,9 +646,9 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
 template <int G, int ESIZE>
 struct QuantPackOccupancy { static constexpr int WAVES_PER_SIMD = (G * ESIZE <= 128) ? 4 : 1; };
 
-// One workgroup per batch of TILES tiles, in two rounds.  Round 1: lane i examines tile i (Eq. 3, pivot
+// One workgroup per batch of TILES tiles, in two stages.  Stage one: lane i examines tile i (Eq. 3, pivot
 // swap in LDS).  The tiles are then regrouped by class -- (plain | transformed) x (narrow | wide) -- so that in
-// round 2, where lane p takes the p-th tile in class order, most wavefronts hold a single class: the
+// stage two, where lane p takes the p-th tile in class order, most wavefronts hold a single class: the
 // Hadamard butterfly runs only in the wavefronts that hold transformed tiles, and the two packing
 // paths rarely both run.  The payload buffer reuses the rows' LDS once every lane holds its tile in
 // registers, which keeps the workgroup small enough for four to share a compute unit: this kernel
@@ -686,7 +686,7 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     tile_pos<B::TILES, LOW>(meta, tid, &b, &rel, &total4);
     __syncthreads();
 
-    // round 1: my own tile
+    // stage one: my own tile
     const bool valid = (uint32_t)tid < nvalid;
     uint32_t cls = 4;                            // tiles past the end sort last
     if (valid) {
@@ -713,7 +713,7 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     }
     __syncthreads();
 
-    // round 2: the tid-th tile in class order
+    // stage two: the tid-th tile in class order
     float x[G];
     uint32_t t = 0, inf = 0;
     if (valid) {

@@ -576,7 +576,7 @@ def test_two_bit_codes_fill_a_quarter_byte_each_in_element_order():
 
 # -------------------------------------------------------------- format
 
-def test_packed_size_closed_form_and_survey_table():
+def test_packed_size_closed_form_and_expected_sizes():
     # Sec. 3.4: the stream's shape depends on the configuration only.
     want = {1: 38144, 2: 2175040, 3: 13942848, 4: 130809920, 5: 111083584}
     for i, w in enumerate(workloads.CONFIGS, 1):
