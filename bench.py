@@ -61,7 +61,7 @@ def cpu_baseline(index, w, alloc_tile, low_bits, budget):
     import workloads
     from oracle import o32
     batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
-    ws, x = workloads.generate(index, batch=batch)
+    ws, x = workloads.generate(index, batch=batch, seq=w.seq, hidden=w.hidden)
     ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, w.tile, ws.dtype, budget, alloc_tile=alloc_tile, low_bits=low_bits)
     t0 = time.perf_counter()
     packed = o32.encode(ocfg, x)
@@ -170,6 +170,9 @@ def main():
     ap.add_argument("--alloc-tile", type=int, default=0,
                     help="allocation tile A in channels, a multiple of the tile width (default 0: A = G, the "
                          "metric's configuration)")
+    ap.add_argument("--shape", type=str, default=None,
+                    help="BxSxC: the chosen configuration's recipe at another shape, e.g. 2x1024x1600 for a "
+                         "GPT2-XL-sized micro-batch (default: the configuration's own shape)")
     ap.add_argument("--tile", type=int, default=0, choices=(0, 8, 16, 32, 64, 128),
                     help="quantization tile G (default 0: the workload's own)")
     ap.add_argument("--low-bits", type=int, default=0, choices=(0, 2, 3),
@@ -200,7 +203,11 @@ def main():
     torch.cuda.set_device(0)
     tahq.binding._load()
 
-    w, x = workloads.generate(args.config)
+    if args.shape:
+        B_, S_, C_ = (int(v) for v in args.shape.lower().split("x"))
+        w, x = workloads.generate(args.config, batch=B_, seq=S_, hidden=C_)
+    else:
+        w, x = workloads.generate(args.config)
     if args.tile:
         import dataclasses
         w = dataclasses.replace(w, tile=args.tile)
@@ -299,7 +306,7 @@ def main():
     dom_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
     achieved = alg[dominant] / (dom_ms * 1e-3) / 1e9
     # the stored counter readings belong to the metric's own configuration
-    stock = not wide and args.low_bits in (0, 3) and budget == w.budget_bits and not args.tile
+    stock = not wide and args.low_bits in (0, 3) and budget == w.budget_bits and not args.tile and not args.shape
     traffic = TRAFFIC_BYTES.get((w.name, dominant)) if stock else None
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

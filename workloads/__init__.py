@@ -123,12 +123,16 @@ def _cfg5(w, rng):
 _RECIPES = (_cfg1, _cfg2, _cfg3, _cfg4, _cfg5)
 
 
-def generate(index, batch=None, seq=None):
-    """Tensor of configuration `index` (1-based), optionally with fewer samples / tokens.
+def generate(index, batch=None, seq=None, hidden=None):
+    """Tensor of configuration `index` (1-based), optionally with fewer samples / tokens, or with the
+    configuration's recipe applied to another hidden size (the name then says so).
 
     Returns (workload, array): array is float32 [B,S,C] or uint16 (bf16 bits) [B,S,C]."""
     base = CONFIGS[index - 1]
     w = base.with_shape(batch, seq)
+    if hidden is not None and hidden != base.hidden:
+        w = Workload(f"{base.name}_recipe_at_{w.batch}x{w.seq}x{hidden}", w.dtype, w.batch, w.seq, hidden, w.tile,
+                     w.budget_bits, w.seed)
     rng = np.random.Generator(np.random.PCG64(w.seed))
     out = np.empty((w.batch, w.seq, w.hidden), np.float32 if w.dtype == F32 else np.uint16)
     for i, x in enumerate(_RECIPES[index - 1](w, rng)):
