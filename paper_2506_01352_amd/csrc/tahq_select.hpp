@@ -385,14 +385,15 @@ __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict_
 // ---- small ranking units: the whole selection in one launch
 
 constexpr uint32_t kSmallUnitThreads = 1024;
-constexpr uint32_t kSmallUnitMaxKeys = 32768;    // 32 keys per thread (beyond that the multi-launch selection is faster)
+constexpr uint32_t kSmallUnitMaxKeys = 65536;    // 64 keys per thread
 
 // A ranking unit of at most 1024 * KPT keys, ranked by ONE workgroup that keeps the keys in registers: the
 // three radix passes run on an LDS histogram, the per-group counts and their prefix sums stay in LDS, and
 // the bit map and rank table (or, for units that do not start on 64-tile boundaries, one byte per tile and
 // the rank entries of the 64-tile groups) are written at the end.  Same result as k_radix_pass x 3,
 // k_seg_count and k_assign, in one launch instead of five: small tensors are bound by launch latency.
-// Thread (wave w, lane l) holds, for r = 0 .. KPT-1, the key of tile 64 * (16 r + w) + l of the unit.
+// Wavefront w owns the KPT consecutive 64-tile groups KPT*w ..: thread (w, lane l) holds, for r = 0 .. KPT-1, the
+// key of tile 64 * (KPT w + r) + l of the unit.  KPT <= 64.
 template <int KPT>
 __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float *__restrict__ H, uint32_t n, uint32_t k,
                                                                     uint64_t *__restrict__ bitmap,
@@ -415,13 +416,17 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     const float *uH = H + (uint64_t)u * n;
     const uint64_t below = (1ull << lane) - 1ull;
 
-    uint32_t key[KPT];
+    // all loads first (from a clamped index, so that none of them sits behind a branch), then the keys
+    float h[KPT];
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
-        const uint32_t i = (uint32_t)(16 * r + wave) * 64u + lane;
-        key[r] = i < n ? order_key(uH[i]) : 0u;
+        const uint32_t i = (uint32_t)(KPT * wave + r) * 64u + lane;
+        h[r] = uH[i < n ? i : n - 1];
     }
-    auto in_unit = [&](int r) { return (uint32_t)(16 * r + wave) * 64u + lane < n; };
+    uint32_t key[KPT];
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) key[r] = order_key(h[r]);
+    auto in_unit = [&](int r) { return (uint32_t)(KPT * wave + r) * 64u + lane < n; };
 
     uint32_t want = k, hi = 0;
 #pragma unroll
@@ -474,17 +479,16 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     }
     const uint32_t thr = hi, take = want;        // the k-th largest key, and how many tiles equal to it are taken
 
-    // per 64-tile group: keys equal to thr, keys above it
+    // per 64-tile group: keys equal to thr, keys above it; lane r keeps the counts of the wavefront's r-th group
+    uint32_t my_eq = 0, my_gt = 0;
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
         const bool ok = in_unit(r);
-        const uint64_t eqm = __ballot(ok && key[r] == thr);
-        const uint64_t gtm = __ballot(ok && key[r] > thr);
-        if (lane == 0) {
-            grp_eq[16 * r + wave] = (uint32_t)__popcll(eqm);
-            grp_sel[16 * r + wave] = (uint32_t)__popcll(gtm);
-        }
+        const uint32_t ne = (uint32_t)__popcll(__ballot(ok && key[r] == thr));
+        const uint32_t ng = (uint32_t)__popcll(__ballot(ok && key[r] > thr));
+        if (lane == r) { my_eq = ne; my_gt = ng; }
     }
+    if (lane < KPT) { grp_eq[KPT * wave + lane] = my_eq; grp_sel[KPT * wave + lane] = my_gt; }
     __syncthreads();
     if (tid < 64) {
         // lane l owns the PER consecutive groups PER*l ..: equal keys before each group (they are taken in index
@@ -508,22 +512,31 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
         for (int i = 0; i < PER; ++i) { grp_sel[lane * PER + i] = rank_before; rank_before += c[i]; }
     }
     __syncthreads();
+    // lane r fetches what the wavefront's r-th group needs; inside the loop it is read from that lane
+    const uint32_t my_eq_before = lane < KPT ? grp_eq[KPT * wave + lane] : 0u;
+    const uint32_t my_rank = u * k + (lane < KPT ? grp_sel[KPT * wave + lane] : 0u);
+    uint64_t my_word = 0;
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
-        const uint32_t g = (uint32_t)(16 * r + wave);
         const bool ok = in_unit(r);
         const bool eq = ok && key[r] == thr;
         const uint64_t eqm = __ballot(eq);
-        const bool sel = ok && (key[r] > thr || (eq && grp_eq[g] + (uint32_t)__popcll(eqm & below) < take));
+        const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)my_eq_before, r);
+        const bool sel = ok && (key[r] > thr || (eq && eq_before + (uint32_t)__popcll(eqm & below) < take));
         const uint64_t selm = __ballot(sel);
-        const uint64_t jg = (uint64_t)u * n + (uint64_t)g * 64u + lane;     // tile index in the tensor
-        const uint32_t rank = u * k + grp_sel[g];
-        if (aligned) {
-            if (lane == 0 && ok) { bitmap[jg >> 6] = selm; ranks[jg >> 6] = rank; }
-        } else if (ok) {
+        if (lane == r) my_word = selm;
+        if (!aligned && ok) {
+            const uint64_t jg = (uint64_t)u * n + (uint64_t)(KPT * wave + r) * 64u + lane;     // tile index in the tensor
             sel_bytes[jg] = sel ? 1 : 0;
-            if ((jg & 63u) == 0) ranks[jg >> 6] = rank + (uint32_t)__popcll(selm & below);
+            if ((jg & 63u) == 0)
+                ranks[jg >> 6] = (uint32_t)__builtin_amdgcn_readlane((int)my_rank, r) + (uint32_t)__popcll(selm & below);
         }
+    }
+    if (aligned && lane < KPT && (uint32_t)(KPT * wave + lane) * 64u < n) {
+        // units start on 64-tile boundaries: lane r writes the word and the rank entry of the r-th group
+        const uint64_t word = ((uint64_t)u * n >> 6) + (uint32_t)(KPT * wave + lane);
+        bitmap[word] = my_word;
+        ranks[word] = my_rank;
     }
 }
 
