@@ -358,10 +358,8 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
             const dim3 grid(s.U), block(kSmallUnitThreads);
             if (n32 <= 16 * kSmallUnitThreads)
                 hipLaunchKernelGGL((k_select_small<16>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
-            else if (n32 <= 32 * kSmallUnitThreads)
-                hipLaunchKernelGGL((k_select_small<32>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
             else
-                hipLaunchKernelGGL((k_select_small<64>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
+                hipLaunchKernelGGL((k_select_small<32>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
             if (wide)
                 hipLaunchKernelGGL(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
                                    (const uint8_t *)sel, (const uint32_t *)ranks_a, (uint32_t)s.T, s.m, bitmap, ranks);

@@ -385,7 +385,8 @@ __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict_
 // ---- small ranking units: the whole selection in one launch
 
 constexpr uint32_t kSmallUnitThreads = 1024;
-constexpr uint32_t kSmallUnitMaxKeys = 65536;    // 64 keys per thread
+constexpr uint32_t kSmallUnitMaxKeys = 32768;    // 32 keys per thread; beyond that the keys no longer fit the
+                                                 // register file of a 1024-thread workgroup and the multi-launch path is as fast
 
 // A ranking unit of at most 1024 * KPT keys, ranked by ONE workgroup that keeps the keys in registers: the
 // three radix passes run on an LDS histogram, the per-group counts and their prefix sums stay in LDS, and
@@ -393,7 +394,7 @@ constexpr uint32_t kSmallUnitMaxKeys = 65536;    // 64 keys per thread
 // the rank entries of the 64-tile groups) are written at the end.  Same result as k_radix_pass x 3,
 // k_seg_count and k_assign, in one launch instead of five: small tensors are bound by launch latency.
 // Wavefront w owns the KPT consecutive 64-tile groups KPT*w ..: thread (w, lane l) holds, for r = 0 .. KPT-1, the
-// key of tile 64 * (KPT w + r) + l of the unit.  KPT <= 64.
+// key of tile 64 * (KPT w + r) + l of the unit.  KPT is 16 or 32.
 template <int KPT>
 __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float *__restrict__ H, uint32_t n, uint32_t k,
                                                                     uint64_t *__restrict__ bitmap,
@@ -479,64 +480,68 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     }
     const uint32_t thr = hi, take = want;        // the k-th largest key, and how many tiles equal to it are taken
 
-    // per 64-tile group: keys equal to thr, keys above it; lane r keeps the counts of the wavefront's r-th group
-    uint32_t my_eq = 0, my_gt = 0;
+    // Keys equal to thr are taken in index order until `take` are used up, so every group needs the number of
+    // equal keys before it: lane r keeps the count of the wavefront's r-th group, wavefront 0 scans the groups.
+    uint32_t my_eq = 0;
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
-        const bool ok = in_unit(r);
-        const uint32_t ne = (uint32_t)__popcll(__ballot(ok && key[r] == thr));
-        const uint32_t ng = (uint32_t)__popcll(__ballot(ok && key[r] > thr));
-        if (lane == r) { my_eq = ne; my_gt = ng; }
+        const uint32_t ne = (uint32_t)__popcll(__ballot(in_unit(r) && key[r] == thr));
+        if (lane == r) my_eq = ne;
     }
-    if (lane < KPT) { grp_eq[KPT * wave + lane] = my_eq; grp_sel[KPT * wave + lane] = my_gt; }
+    if (lane < KPT) grp_eq[KPT * wave + lane] = my_eq;
     __syncthreads();
+    constexpr int PER = NG / 64;                 // lane l of wavefront 0 scans the PER consecutive groups PER*l ..
     if (tid < 64) {
-        // lane l owns the PER consecutive groups PER*l ..: equal keys before each group (they are taken in index
-        // order until `take` are used up), then wide tiles before each group
-        constexpr int PER = NG / 64;
-        uint32_t e[PER], c[PER], esum = 0;
+        uint32_t e[PER], esum = 0;
 #pragma unroll
         for (int i = 0; i < PER; ++i) { e[i] = grp_eq[lane * PER + i]; esum += e[i]; }
         uint32_t eq_before = wave_incl_scan(esum) - esum;
-        uint32_t csum = 0;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const uint32_t left = eq_before < take ? take - eq_before : 0u;
-            c[i] = grp_sel[lane * PER + i] + (e[i] < left ? e[i] : left);
-            grp_eq[lane * PER + i] = eq_before;
-            eq_before += e[i];
-            csum += c[i];
-        }
-        uint32_t rank_before = wave_incl_scan(csum) - csum;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) { grp_sel[lane * PER + i] = rank_before; rank_before += c[i]; }
+        for (int i = 0; i < PER; ++i) { grp_eq[lane * PER + i] = eq_before; eq_before += e[i]; }
     }
     __syncthreads();
-    // lane r fetches what the wavefront's r-th group needs; inside the loop it is read from that lane
+    // the width bit of every tile; lane r keeps the bit map word and the count of the wavefront's r-th group
     const uint32_t my_eq_before = lane < KPT ? grp_eq[KPT * wave + lane] : 0u;
-    const uint32_t my_rank = u * k + (lane < KPT ? grp_sel[KPT * wave + lane] : 0u);
     uint64_t my_word = 0;
 #pragma unroll
     for (int r = 0; r < KPT; ++r) {
         const bool ok = in_unit(r);
         const bool eq = ok && key[r] == thr;
         const uint64_t eqm = __ballot(eq);
-        const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)my_eq_before, r);
-        const bool sel = ok && (key[r] > thr || (eq && eq_before + (uint32_t)__popcll(eqm & below) < take));
+        bool sel = ok && key[r] > thr;
+        if (eqm) {                               // rare: at most a few groups hold keys equal to the threshold
+            const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)my_eq_before, r);
+            sel = sel || (eq && eq_before + (uint32_t)__popcll(eqm & below) < take);
+        }
         const uint64_t selm = __ballot(sel);
         if (lane == r) my_word = selm;
-        if (!aligned && ok) {
-            const uint64_t jg = (uint64_t)u * n + (uint64_t)(KPT * wave + r) * 64u + lane;     // tile index in the tensor
-            sel_bytes[jg] = sel ? 1 : 0;
-            if ((jg & 63u) == 0)
-                ranks[jg >> 6] = (uint32_t)__builtin_amdgcn_readlane((int)my_rank, r) + (uint32_t)__popcll(selm & below);
-        }
+        if (!aligned && ok) sel_bytes[(uint64_t)u * n + (uint64_t)(KPT * wave + r) * 64u + lane] = sel ? 1 : 0;
     }
-    if (aligned && lane < KPT && (uint32_t)(KPT * wave + lane) * 64u < n) {
-        // units start on 64-tile boundaries: lane r writes the word and the rank entry of the r-th group
-        const uint64_t word = ((uint64_t)u * n >> 6) + (uint32_t)(KPT * wave + lane);
-        bitmap[word] = my_word;
-        ranks[word] = my_rank;
+    if (lane < KPT) grp_sel[KPT * wave + lane] = (uint32_t)__popcll(my_word);
+    __syncthreads();
+    if (tid < 64) {
+        uint32_t c[PER], csum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { c[i] = grp_sel[lane * PER + i]; csum += c[i]; }
+        uint32_t rank_before = wave_incl_scan(csum) - csum;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { grp_sel[lane * PER + i] = rank_before; rank_before += c[i]; }
+    }
+    __syncthreads();
+    // lane r writes what belongs to the wavefront's r-th group
+    const uint32_t g = (uint32_t)(KPT * wave + lane);
+    if (lane < KPT && g * 64u < n) {
+        const uint32_t rank = u * k + grp_sel[g];            // wide tiles before the group, in the whole tensor
+        const uint64_t j0 = (uint64_t)u * n + (uint64_t)g * 64u;     // the group's first tile in the tensor
+        if (aligned) {
+            bitmap[j0 >> 6] = my_word;
+            ranks[j0 >> 6] = rank;
+        } else {
+            // units do not start on 64-tile boundaries: the rank-table entry of the boundary inside this group
+            // (if the group still reaches it)
+            const uint32_t p = (uint32_t)((64u - (uint32_t)(j0 & 63u)) & 63u);        // distance to the boundary
+            if (g * 64u + p < n) ranks[(j0 + p) >> 6] = rank + (uint32_t)__popcll(my_word & ((1ull << p) - 1ull));
+        }
     }
 }
 
