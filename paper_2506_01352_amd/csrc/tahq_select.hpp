@@ -8,6 +8,9 @@
 //   * per segment of tiles, counts of keys == K* and > K* ; their prefix sums give every tile
 //     its place among the equal keys (index order) and every 64-tile group its rank-table entry.
 //
+// Ranking units of at most 32768 tiles skip all of this: k_select_small ranks such a unit with one workgroup in one
+// launch (keys in registers, histograms in LDS), because at that size the five launches cost more than the work.
+//
 // Kernels never wait on each other inside a launch: every dependency is a launch boundary, and the
 // small reductions a later kernel needs (which bin holds the k-th key, prefix over segments) are
 // recomputed by every block from a few KB of global data.
