@@ -541,3 +541,43 @@ def test_decoding_a_damaged_stream_stays_inside_its_buffers(tahq, G, low):
             out.check()
             packed.check()
             assert np.array_equal(packed.view.cpu().numpy(), host)     # the stream is only read
+
+
+def _random_configurations(count, seed):
+    """Seeded sweep over the configuration space: tile width, dtype, widths, budget, allocation tile, scope,
+    tau, shapes with ragged batches and ranking units on both sides of the single-launch threshold."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        G = int(rng.choice([8, 16, 32, 64, 128]))
+        M = int(rng.choice([1, 2, 3, 5, 8, 12, 25]))                 # tiles per token
+        Cc = G * M
+        B = int(rng.choice([1, 2, 3, 5]))
+        S = int(rng.choice([1, 3, 17, 64, 200, 513, 1500]))
+        if B * S * Cc > 6_000_000:
+            continue
+        low = int(rng.choice([3, 3, 2]))
+        budget = float(np.float32(low + rng.choice([0.0, 1.0, rng.uniform(0.02, 0.98)])))
+        divisors = [d for d in range(1, M + 1) if M % d == 0]
+        m = int(rng.choice(divisors)) if rng.random() < 0.4 else 1
+        out.append(dict(B=B, S=S, Cc=Cc, G=G, dtype=int(rng.integers(0, 2)), budget=budget, low_bits=low,
+                        alloc_tile=G * m if m > 1 else 0, scope=int(rng.random() < 0.25),
+                        tau=float(rng.choice([2.0, 2.0, 1.25, 6.0])), out_dtype=int(rng.integers(0, 2)),
+                        data_seed=int(rng.integers(0, 2 ** 31))))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_configurations(120, seed=2024), ids=lambda c: "{B}x{S}x{Cc}_g{G}_d{dtype}_lo{low_bits}_a{alloc_tile}_s{scope}".format(**c))
+def test_random_configurations_bit_exact(tahq, case):
+    c = case
+    rng = np.random.default_rng(c["data_seed"])
+    x = rng.standard_normal((c["B"], c["S"], c["Cc"])).astype(np.float32)
+    x *= np.exp(rng.standard_normal((c["B"], c["S"], 1))).astype(np.float32)        # token scales
+    x[:, :, ::max(1, c["Cc"] // 7)] *= 30.0                                           # outlier channels
+    if c["S"] > 4:
+        x[:, ::5, :] = 0.0                                                            # ties at entropy 0
+        x[:, 1::7, :] = -2.5                                                          # ties at entropy ln G
+    xin = x if c["dtype"] == 0 else workloads.f32_to_bf16_bits(x)
+    _say(f"[case] random configuration {c}")
+    check_case(tahq, xin, c["B"], c["S"], c["Cc"], c["G"], c["dtype"], c["budget"], out_dtype=c["out_dtype"],
+               low_bits=c["low_bits"], alloc_tile=c["alloc_tile"], scope=c["scope"], tau=c["tau"])
