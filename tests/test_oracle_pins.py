@@ -501,6 +501,72 @@ def test_small_tiles_and_hidden_1600_streams_parse_and_decode_in_float64(G, C_, 
     assert np.all(err <= sf / 2 * math.sqrt(G) * (1 + 1e-3) + 1e-6 * np.abs(xf).max(axis=1))
 
 
+# ------------------------- a seeded sweep over combinations of the options
+
+def _sweep_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        G = int(rng.choice([8, 16, 32, 64, 128]))
+        M = int(rng.choice([1, 2, 3, 4, 6, 10]))
+        B, S = int(rng.choice([1, 2, 3])), int(rng.choice([1, 5, 23, 70]))
+        low = int(rng.choice([3, 3, 2]))
+        divisors = [d for d in range(1, M + 1) if M % d == 0]
+        m = int(rng.choice(divisors)) if rng.random() < 0.5 else 1
+        out.append(dict(B=B, S=S, G=G, M=M, dtype=int(rng.integers(0, 2)), low=low, m=m, scope=int(rng.random() < 0.3),
+                        budget=float(np.float32(low + rng.choice([0.0, 1.0, rng.uniform(0.05, 0.95)]))),
+                        tau=float(rng.choice([2.0, 1.5, 5.0])), seed=int(rng.integers(0, 2 ** 31))))
+    return out
+
+
+@pytest.mark.parametrize("c", _sweep_cases(40, seed=77), ids=lambda c: "{B}x{S}x{M}tiles_g{G}_d{dtype}_lo{low}_m{m}_s{scope}".format(**c))
+def test_option_combinations_parse_and_decode_independently_in_float64(c):
+    # every combination of tile width, dtype, widths, allocation tile, scope and tau goes through the independent
+    # float64 statement: size, header, allocation from the entropies, rank table, pivots, coverage, decode, error bound
+    rng = np.random.default_rng(c["seed"])
+    B, S, G, M, low, m = c["B"], c["S"], c["G"], c["M"], c["low"], c["m"]
+    Cc = G * M
+    x = rng.standard_normal((B, S, Cc)).astype(np.float32) * np.exp(rng.standard_normal((B, S, 1))).astype(np.float32)
+    x[:, :, ::max(1, Cc // 5)] *= 25.0
+    if S > 4:
+        x[:, ::4, :] = 0.0
+    xin = workloads.f32_to_bf16_bits(x) if c["dtype"] else x
+    cfg = o32.make_cfg(B, S, Cc, G, c["dtype"], c["budget"], tau=c["tau"], scope=c["scope"], alloc_tile=G * m if m > 1 else 0,
+                       low_bits=low)
+    U = 1 if c["scope"] else B
+    T = o32.n_tiles(cfg)
+    kA = o32.k_per_unit(cfg)
+    assert kA == o64.k_per_unit(T // m // U, np.float32(c["budget"]), low=low)
+    packed = o32.encode(cfg, xin)
+    assert packed.size == o32.packed_size(cfg) == o64.section_offsets(T, G, U, kA * m, low=low)["total"]
+    out64, s = o64.decode_stream(packed, T, G, U, kA * m, low=low)
+    hdr = s["header"].view("<u4")
+    assert list(hdr[1:9]) == [1, c["dtype"], B, S, Cc, G, c["scope"], kA] and hdr[14] == G * m and hdr[15] == low
+    xf = (workloads.bf16_bits_to_f32(xin) if c["dtype"] else x).astype(np.float64)
+    HA = o32.alloc_entropies(cfg, xin)
+    assert np.max(np.abs(HA - o64.entropy(xf.reshape(-1, G * m)))) < 5e-5
+    assert np.array_equal(s["width"], np.repeat(o64.allocate(HA, U, kA, low=low), m))
+    assert np.array_equal(s["ranks"], s["rank_of"][::64])
+    flag64, d64 = o64.outlier(xf.reshape(T, G), tau=c["tau"])
+    _, pivot, mn, mx = o32.tile_stats(cfg, xin)
+    assert np.array_equal(s["pivot"], pivot)
+    # float64 and fp32 agree on the outlier test except within rounding of the threshold
+    a = np.sort(np.abs(xf.reshape(T, G)), axis=1)
+    clear = np.abs(a[:, -1] - c["tau"] * (a[:, -2] + 1e-8)) > 1e-5 * np.maximum(a[:, -1], 1e-30)
+    assert np.array_equal((pivot >> 7)[clear], flag64.astype(np.uint8)[clear])
+    assert np.array_equal((pivot & 0x7F)[flag64 & clear], d64[flag64 & clear])
+    sf = s["scale"].astype(np.float64); zf = s["zero"].astype(np.float64)
+    L = (1 << s["width"]) - 1
+    # the step is (max - zero)/L rounded to fp32 and then up to binary16: the coded range reaches the maximum up to
+    # that one fp32 rounding (when the quotient is itself a binary16 value, rounding up adds no slack)
+    assert np.all(zf <= mn) and np.all(zf + L * sf >= mx - 2.0 ** -22 * (mx - zf)) and np.all(s["codes"] <= L[:, None])
+    out32 = o32.decode(cfg, packed, o32.F32).reshape(T, G).astype(np.float64)
+    scale = np.maximum(np.abs(out64).max(axis=1, keepdims=True), 1e-30)
+    assert np.max(np.abs(out32 - out64) / scale) < 1e-5
+    err = np.linalg.norm(out64 - xf.reshape(T, G), axis=1)
+    assert np.all(err <= sf / 2 * math.sqrt(G) * (1 + 1e-3) + 1e-6 * np.abs(xf.reshape(T, G)).max(axis=1))
+
+
 # ------------------------------------------- the INT2/INT3 mix (lo = 2)
 
 def test_low_bits_changes_the_two_widths_the_budget_range_and_the_count():
