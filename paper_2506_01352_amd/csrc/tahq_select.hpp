@@ -164,14 +164,18 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
     constexpr int R = 16;
     const uint64_t stride = (uint64_t)gridDim.x * 256;
     for (uint64_t base = (uint64_t)blockIdx.x * 256 + tid; base < n; base += R * stride) {
+        // all loads first, from a clamped index: a load behind a branch would wait for the one before it
+        float h[R];
         uint32_t key[R];
         bool ok[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const uint64_t i = base + r * stride;
             ok[r] = i < n;
-            key[r] = ok[r] ? order_key(uH[i]) : 0u;
+            h[r] = uH[ok[r] ? i : (uint64_t)n - 1];
         }
+#pragma unroll
+        for (int r = 0; r < R; ++r) key[r] = order_key(h[r]);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             bool active = ok[r] && (PASS == 0 || (key[r] >> hi_shift) == want_hi);
@@ -236,14 +240,17 @@ __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, 
     const float *uH = H + (uint64_t)u * n;
     uint32_t eq = 0, gt = 0;
     for (int r0 = 0; r0 < (int)(kSegTiles / 64); r0 += 8) {
+        float h[8];
         uint32_t key[8];
         bool ok[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint64_t j = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
             ok[r] = j < n;
-            key[r] = ok[r] ? order_key(uH[j]) : 0u;
+            h[r] = uH[ok[r] ? j : (uint64_t)n - 1];       // clamped: no load waits behind a branch
         }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) key[r] = order_key(h[r]);
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             eq += (uint32_t)__popcll(__ballot(ok[r] && key[r] == thr));
@@ -323,14 +330,17 @@ __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uin
     uint32_t eq_run = base_eq[wave], rank_run = base_rank[wave];
     const uint64_t below = (1ull << lane) - 1ull;
     for (int r0 = 0; r0 < (int)(kSegTiles / 64); r0 += 8) {
+        float h[8];
         uint32_t key[8];
         bool ok[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
             ok[r] = jl < n;
-            key[r] = ok[r] ? order_key(uH[jl]) : 0u;
+            h[r] = uH[ok[r] ? jl : (uint64_t)n - 1];      // clamped: no load waits behind a branch
         }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) key[r] = order_key(h[r]);
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
