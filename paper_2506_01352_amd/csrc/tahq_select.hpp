@@ -100,11 +100,11 @@ __device__ __forceinline__ void pick_bin_two_level(const uint32_t *__restrict__ 
 #pragma unroll
     for (uint32_t i = 0; i < 32; ++i) {
         const uint32_t blk = ((uint32_t)lane >> 5) + 2 * i;
-        part[i] = blk < hb ? partial[(uint64_t)blk * kHistBins + sb * 32 + b_in] : 0u;
+        part[i] = partial[(uint64_t)(blk < hb ? blk : 0u) * kHistBins + sb * 32 + b_in];    // clamped, not branched
     }
     uint32_t sum = 0;
 #pragma unroll
-    for (uint32_t i = 0; i < 32; ++i) sum += part[i];
+    for (uint32_t i = 0; i < 32; ++i) sum += (((uint32_t)lane >> 5) + 2 * i) < hb ? part[i] : 0u;
     sum += (uint32_t)__shfl_xor((int)sum, 32, 64);
     const uint32_t mine = lane < 32 ? sum : 0u;
     const uint32_t above2 = wave_incl_scan(mine) - mine;
@@ -293,8 +293,11 @@ __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uin
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t sidx = base + (uint32_t)lane * 8 + i;
-                e[i] = sidx < s0 ? pairs[sidx] : make_uint2(0u, 0u);
+                e[i] = pairs[sidx < s0 ? sidx : 0u];                 // clamped, not branched; masked below
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (base + (uint32_t)lane * 8 + i >= s0) e[i] = make_uint2(0u, 0u);
             uint32_t eq_sum = 0;
 #pragma unroll
             for (int i = 0; i < 8; ++i) eq_sum += e[i].x;
@@ -314,7 +317,10 @@ __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uin
         // the block's own four segments, in order
         uint2 own[4];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) own[w] = s0 + w < nseg ? pairs[s0 + w] : make_uint2(0u, 0u);
+        for (int w = 0; w < 4; ++w) own[w] = pairs[s0 + w < nseg ? s0 + w : nseg - 1];
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            if (s0 + w >= nseg) own[w] = make_uint2(0u, 0u);
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             if (lane == 0) { base_eq[w] = eq_run; base_rank[w] = rank_run; }

@@ -461,10 +461,12 @@ __device__ __forceinline__ void load_meta(const uint8_t *__restrict__ packed, co
 {
     const uint64_t *bitmap = reinterpret_cast<const uint64_t *>(packed + lay.bitmap) + lane_zero;
     const uint32_t *ranks = reinterpret_cast<const uint32_t *>(packed + lay.ranks) + lane_zero;
+    const uint64_t last_word = ((uint64_t)T - 1) >> 6;
 #pragma unroll
     for (int w = 0; w < BatchMeta<TILES>::WORDS; ++w) {
         const uint64_t jw = (j0 >> 6) + w;
-        m.word[w] = jw * 64 < T ? bitmap[jw] : 0ull;
+        const uint64_t word = bitmap[jw <= last_word ? jw : last_word];     // clamped index: no load behind a branch
+        m.word[w] = jw <= last_word ? word : 0ull;
     }
     m.rank0 = ranks[j0 >> 6];
 }
