@@ -138,6 +138,19 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
 
     for (int i = tid; i < BINS; i += 256) lh[i] = 0;
 
+    // every thread walks the unit's keys in steps of the grid, sixteen loads in flight at a time; the first
+    // sixteen are issued before the bin of the previous pass is worked out, which they do not depend on.
+    // All loads use a clamped index: a load behind a branch would wait for the one before it.
+    constexpr int R = 16;
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t base0 = (uint64_t)blockIdx.x * 256 + tid;
+    float h[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint64_t i = base0 + r * stride;
+        h[r] = uH[i < n ? i : (uint64_t)n - 1];
+    }
+
     uint32_t want_hi = 0;
     if (PASS > 0) {
         if (tid < 64) {
@@ -160,22 +173,22 @@ __global__ __launch_bounds__(256) void k_radix_pass(const float *__restrict__ H,
     constexpr uint32_t mask = PASS == 0 ? 1023u : 2047u;
     constexpr int hi_shift = PASS == 1 ? 22 : 11;
 
-    // every thread walks the unit's keys in steps of the grid; sixteen loads are in flight at a time
-    constexpr int R = 16;
-    const uint64_t stride = (uint64_t)gridDim.x * 256;
-    for (uint64_t base = (uint64_t)blockIdx.x * 256 + tid; base < n; base += R * stride) {
-        // all loads first, from a clamped index: a load behind a branch would wait for the one before it
-        float h[R];
+    for (uint64_t base = base0; base < n; base += R * stride) {
         uint32_t key[R];
         bool ok[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const uint64_t i = base + r * stride;
-            ok[r] = i < n;
-            h[r] = uH[ok[r] ? i : (uint64_t)n - 1];
+            ok[r] = base + r * stride < n;
+            key[r] = order_key(h[r]);
         }
+        // the next sixteen, while these are counted
+        if (base + R * stride < n) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) key[r] = order_key(h[r]);
+            for (int r = 0; r < R; ++r) {
+                const uint64_t i = base + (R + r) * stride;
+                h[r] = uH[i < n ? i : (uint64_t)n - 1];
+            }
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             bool active = ok[r] && (PASS == 0 || (key[r] >> hi_shift) == want_hi);
@@ -222,6 +235,17 @@ __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, 
     const uint32_t u = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t *ust = state + (uint64_t)u * 8;
+    // my wavefront's segment: its sixteen keys per lane are requested first (clamped index, nothing behind a
+    // branch); the threshold they are compared with is worked out while they arrive
+    constexpr int KEYS = (int)(kSegTiles / 64);
+    const uint32_t s = blockIdx.x * 4 + wave;
+    const float *uH = H + (uint64_t)u * n;
+    float h[KEYS];
+#pragma unroll
+    for (int r = 0; r < KEYS; ++r) {
+        const uint64_t j = (uint64_t)s * kSegTiles + (uint64_t)r * 64 + lane;
+        h[r] = uH[j < n ? j : (uint64_t)n - 1];
+    }
     if (tid < 64) {
         uint32_t bin, rem;
         pick_bin_two_level(coarse + ((uint64_t)u * 2 + 1) * 64, partial + ((uint64_t)u * 2 + 1) * hb * kHistBins, hb,
@@ -235,27 +259,14 @@ __global__ __launch_bounds__(256) void k_seg_count(const float *__restrict__ H, 
     }
     __syncthreads();
     const uint32_t thr = chosen[0];
-    const uint32_t s = blockIdx.x * 4 + wave;
     if (s >= nseg) return;
-    const float *uH = H + (uint64_t)u * n;
     uint32_t eq = 0, gt = 0;
-    for (int r0 = 0; r0 < (int)(kSegTiles / 64); r0 += 8) {
-        float h[8];
-        uint32_t key[8];
-        bool ok[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint64_t j = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
-            ok[r] = j < n;
-            h[r] = uH[ok[r] ? j : (uint64_t)n - 1];       // clamped: no load waits behind a branch
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) key[r] = order_key(h[r]);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            eq += (uint32_t)__popcll(__ballot(ok[r] && key[r] == thr));
-            gt += (uint32_t)__popcll(__ballot(ok[r] && key[r] > thr));
-        }
+    for (int r = 0; r < KEYS; ++r) {
+        const bool ok = (uint64_t)s * kSegTiles + (uint64_t)r * 64 + lane < n;
+        const uint32_t key = order_key(h[r]);
+        eq += (uint32_t)__popcll(__ballot(ok && key == thr));
+        gt += (uint32_t)__popcll(__ballot(ok && key > thr));
     }
     if (lane == 0) {
         seg[((uint64_t)u * nseg + s) * 2 + 0] = eq;
@@ -281,6 +292,16 @@ __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uin
     const uint32_t thr = ust[ST_KEY], take = ust[ST_TAKE];
     const uint32_t *useg = seg + (uint64_t)u * nseg * 2;
     const uint32_t s0 = blockIdx.x * 4;
+    // my wavefront's segment: its sixteen keys per lane are requested first (clamped index, nothing behind a
+    // branch) and arrive while the first wavefront sums the counts of the segments before this block
+    constexpr int KEYS = (int)(kSegTiles / 64);
+    const float *uH = H + (uint64_t)u * n;
+    float h[KEYS];
+#pragma unroll
+    for (int r = 0; r < KEYS; ++r) {
+        const uint64_t jl = (uint64_t)(s0 + wave) * kSegTiles + (uint64_t)r * 64 + lane;
+        h[r] = uH[jl < n ? jl : (uint64_t)n - 1];
+    }
 
     if (tid < 64) {
         // Sums over the s0 segments before this block, 512 segments per sweep: lane l owns the 8 consecutive
@@ -332,38 +353,26 @@ __global__ __launch_bounds__(256) void k_assign(const float *__restrict__ H, uin
     __syncthreads();
     const uint32_t s = s0 + wave;
     if (s >= nseg) return;
-    const float *uH = H + (uint64_t)u * n;
     uint32_t eq_run = base_eq[wave], rank_run = base_rank[wave];
     const uint64_t below = (1ull << lane) - 1ull;
-    for (int r0 = 0; r0 < (int)(kSegTiles / 64); r0 += 8) {
-        float h[8];
-        uint32_t key[8];
-        bool ok[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
-            ok[r] = jl < n;
-            h[r] = uH[ok[r] ? jl : (uint64_t)n - 1];      // clamped: no load waits behind a branch
+    for (int r = 0; r < KEYS; ++r) {
+        const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)r * 64 + lane;
+        const bool ok = jl < n;
+        const uint32_t key = order_key(h[r]);
+        const bool eq = ok && key == thr;
+        const uint64_t eq_mask = __ballot(eq);
+        const bool sel = ok && (key > thr || (eq && eq_run + (uint32_t)__popcll(eq_mask & below) < take));
+        const uint64_t sel_mask = __ballot(sel);
+        const uint64_t jg = (uint64_t)u * n + jl;     // tile index in the tensor
+        if (aligned) {
+            if (lane == 0 && ok) { bitmap[jg >> 6] = sel_mask; ranks[jg >> 6] = rank_run; }
+        } else if (ok) {
+            sel_bytes[jg] = sel ? 1 : 0;
+            if ((jg & 63u) == 0) ranks[jg >> 6] = rank_run + (uint32_t)__popcll(sel_mask & below);
         }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) key[r] = order_key(h[r]);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint64_t jl = (uint64_t)s * kSegTiles + (uint64_t)(r0 + r) * 64 + lane;
-            const bool eq = ok[r] && key[r] == thr;
-            const uint64_t eq_mask = __ballot(eq);
-            const bool sel = ok[r] && (key[r] > thr || (eq && eq_run + (uint32_t)__popcll(eq_mask & below) < take));
-            const uint64_t sel_mask = __ballot(sel);
-            const uint64_t jg = (uint64_t)u * n + jl;     // tile index in the tensor
-            if (aligned) {
-                if (lane == 0 && ok[r]) { bitmap[jg >> 6] = sel_mask; ranks[jg >> 6] = rank_run; }
-            } else if (ok[r]) {
-                sel_bytes[jg] = sel ? 1 : 0;
-                if ((jg & 63u) == 0) ranks[jg >> 6] = rank_run + (uint32_t)__popcll(sel_mask & below);
-            }
-            eq_run += (uint32_t)__popcll(eq_mask);
-            rank_run += (uint32_t)__popcll(sel_mask);
-        }
+        eq_run += (uint32_t)__popcll(eq_mask);
+        rank_run += (uint32_t)__popcll(sel_mask);
     }
 }
 
