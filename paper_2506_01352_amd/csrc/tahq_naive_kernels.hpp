@@ -94,11 +94,13 @@ void k_naive_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, 
     const uint32_t nvalid = left < (uint32_t)kNaiveChunks ? left : (uint32_t)kNaiveChunks;
     const uint32_t *src = reinterpret_cast<const uint32_t *>(packed + 64) + (uint64_t)j0 * BITS;
     const uint32_t nwords = nvalid * BITS;
+    // (from a clamped index: a load behind a bounds-check branch would wait for the one before it; words past the
+    // end of a ragged workgroup are never used)
     uint32_t got[BITS];
 #pragma unroll
     for (int i = 0; i < BITS; ++i) {
         const uint32_t p = (uint32_t)i * kNaiveChunks + tid;
-        got[i] = p < nwords ? __builtin_nontemporal_load(src + p) : 0u;
+        got[i] = __builtin_nontemporal_load(src + (p < nwords ? p : nwords - 1));
     }
 #pragma unroll
     for (int i = 0; i < BITS; ++i) pay[skew((uint32_t)i * kNaiveChunks + tid)] = got[i];
