@@ -117,3 +117,25 @@ def test_full_size_gradient_tensor_sampled(tahq):
         lo = 64 + b0 * per * bits // 8
         assert np.array_equal(got[lo:lo + nb * per * bits // 8], want[64:]), f"sample {b0}"
         assert np.array_equal(got_out[b0 * per:(b0 + nb) * per], n32.decode(ocfg, want, n32.BF16)), f"sample {b0}"
+
+
+def _random_naive_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        out.append(dict(B=int(rng.choice([1, 2, 5])), S=int(rng.choice([1, 7, 64, 333])), Cc=32 * int(rng.choice([1, 3, 16, 50, 129])),
+                        dtype=int(rng.integers(0, 2)), bits=int(rng.integers(2, 17)),
+                        scale=float(rng.choice([1.0, 2.0 ** 10, 2.0 ** -4, 3.3, 1e4, 7e-3])), seed=int(rng.integers(0, 2 ** 31))))
+    return out
+
+
+@pytest.mark.parametrize("c", _random_naive_cases(60, seed=99), ids=lambda c: "{B}x{S}x{Cc}_d{dtype}_b{bits}".format(**c))
+def test_random_configurations_bit_exact(tahq, c):
+    rng = np.random.default_rng(c["seed"])
+    span = 2.0 ** (c["bits"] - 1) / c["scale"]
+    x = (rng.standard_normal((c["B"], c["S"], c["Cc"])) * span * 0.5).astype(np.float32)
+    x[..., ::11] *= 4.0                                              # part of it beyond the range
+    x[..., 5::13] = 0.0
+    xin = workloads.f32_to_bf16_bits(x) if c["dtype"] else x
+    _say(f"[case] naive random configuration {c}")
+    check_case(tahq, xin, c["B"], c["S"], c["Cc"], c["dtype"], c["bits"], c["scale"])
