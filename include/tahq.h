@@ -70,7 +70,8 @@ typedef enum {
     TAHQ_ERR_BUFFER_TOO_SMALL = 4,     /* packed capacity / packed_bytes below tahq_packed_size */
     TAHQ_ERR_WORKSPACE_TOO_SMALL = 5,  /* workspace capacity below tahq_workspace_size   */
     TAHQ_ERR_MISALIGNED = 6,           /* a device pointer is not 16-byte aligned        */
-    TAHQ_ERR_HIP = 7                   /* a kernel launch failed                         */
+    TAHQ_ERR_HIP = 7,                  /* a kernel launch failed                         */
+    TAHQ_ERR_TOO_LARGE = 8             /* tahq_encode_noalloc: tahq_workspace_size(cfg) exceeds TAHQ_NOALLOC_MAX_WORKSPACE */
 } tahq_status;
 
 typedef enum { TAHQ_F32 = 0, TAHQ_BF16 = 1 } tahq_dtype;
@@ -125,6 +126,23 @@ tahq_status tahq_encode(const tahq_config *cfg, const void *d_in,
                         void *d_packed, size_t packed_capacity,
                         void *d_workspace, size_t workspace_capacity,
                         tahq_stream stream);
+
+/* tahq_encode for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * tahq_encode, byte for byte; the encoder's scratch is a buffer built into the library (a
+ * file-scope device array of TAHQ_NOALLOC_MAX_WORKSPACE bytes that every GPU the library runs on
+ * holds until the process ends).  The call allocates nothing and frees nothing.
+ *   d_in, d_packed, packed_capacity, stream: as tahq_encode; `stream` must belong to the current device
+ * Errors as tahq_encode, and TAHQ_ERR_TOO_LARGE (nothing enqueued) when tahq_workspace_size(cfg)
+ * exceeds TAHQ_NOALLOC_MAX_WORKSPACE.  The first call on a device looks up that device's copy of
+ * the buffer (hipGetSymbolAddress); make it outside stream capture.
+ * All calls on one GPU share that GPU's buffer: two calls whose kernels may overlap there (different
+ * streams, or host threads that do not order their streams) race; order them, or use tahq_encode
+ * with a workspace per stream.  tahq_decode needs no scratch and has no such variant. */
+#define TAHQ_NOALLOC_MAX_WORKSPACE (32u << 20)
+tahq_status tahq_encode_noalloc(const tahq_config *cfg, const void *d_in,
+                                void *d_packed, size_t packed_capacity,
+                                tahq_stream stream);
 
 /* The encoder's phases, in the order they run.  tahq_encode runs all of them. */
 enum {

@@ -59,6 +59,8 @@ def _load():
     L.tahq_workspace_size.argtypes = [P]
     L.tahq_encode.restype = C.c_int
     L.tahq_encode.argtypes = [P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tahq_encode_noalloc.restype = C.c_int
+    L.tahq_encode_noalloc.argtypes = [P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tahq_encode_phases.restype = C.c_int
     L.tahq_encode_phases.argtypes = [P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32,
                                      C.c_void_p]
@@ -156,6 +158,17 @@ def tahq_encode(cfg, d_in, d_packed, d_workspace, stream=None, packed_capacity=N
                              _stream_handle(stream))
     if rc != 0:
         raise TahqError(rc, "tahq_encode")
+
+
+NOALLOC_MAX_WORKSPACE = 32 << 20     # TAHQ_NOALLOC_MAX_WORKSPACE of include/tahq.h
+
+
+def tahq_encode_noalloc(cfg, d_in, d_packed, stream=None, packed_capacity=None):
+    """tahq_encode on the library's built-in scratch: no workspace argument, nothing allocated."""
+    cap = _nbytes(d_packed) if packed_capacity is None else packed_capacity
+    rc = _load().tahq_encode_noalloc(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_packed), cap, _stream_handle(stream))
+    if rc != 0:
+        raise TahqError(rc, "tahq_encode_noalloc")
 
 
 PHASE_PROLOGUE, PHASE_ENTROPY, PHASE_SELECT, PHASE_QUANT, PHASE_ALL = 1, 2, 4, 8, 15

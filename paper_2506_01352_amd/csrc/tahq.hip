@@ -20,9 +20,22 @@
 #include "tahq_naive_kernels.hpp"
 #include "tahq_naive.h"
 
+#include <mutex>
+
 using namespace tahq;
 
+// Built-in scratch of tahq_encode_noalloc: encoder workspace for callers that cannot provide one.  Every GPU
+// the library runs on holds its own copy of this array, at its own address, until the process ends.
+constexpr size_t kBuiltinScratchBytes = (size_t)TAHQ_NOALLOC_MAX_WORKSPACE;
+static __device__ __align__(256) unsigned char scratch[kBuiltinScratchBytes];
+
 namespace {
+
+// Device address of `scratch` on every device that tahq_encode_noalloc has been called on.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: kernels are given the address kept here.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];
 
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -408,6 +421,37 @@ tahq_status tahq_encode(const tahq_config *cfg, const void *d_in, void *d_packed
                               TAHQ_PHASE_ALL, stream);
 }
 
+tahq_status tahq_encode_noalloc(const tahq_config *cfg, const void *d_in, void *d_packed, size_t packed_capacity,
+                                tahq_stream stream)
+{
+    Shape s;
+    tahq_status rc = make_shape(cfg, &s);
+    if (rc != TAHQ_OK) return rc;
+    Workspace ws;
+    make_workspace(s, &ws);
+    if (ws.total > kBuiltinScratchBytes) return TAHQ_ERR_TOO_LARGE;
+    if (!d_in || !d_packed) return TAHQ_ERR_NULL;
+    Layout lay;
+    make_layout(s, &lay);
+    if (packed_capacity < lay.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
+    if (misaligned(d_in) || misaligned(d_packed)) return TAHQ_ERR_MISALIGNED;
+    // the current device's copy of the built-in scratch: looked up once per device, with that device current
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TAHQ_ERR_HIP;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        ptr = g_scratch_ptr[dev];
+        if (!ptr) {
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TAHQ_ERR_HIP;
+            g_scratch_ptr[dev] = ptr;
+        }
+    }
+    // what must start at zero in there (the selection's histograms and state) is cleared by the encoder's
+    // first kernel, as it is in a caller's workspace
+    return tahq_encode_phases(cfg, d_in, d_packed, packed_capacity, ptr, kBuiltinScratchBytes, TAHQ_PHASE_ALL, stream);
+}
+
 tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t packed_bytes, void *d_out,
                         uint32_t out_dtype, void *d_workspace, size_t workspace_capacity, tahq_stream stream)
 {
@@ -459,6 +503,7 @@ const char *tahq_status_string(tahq_status s)
     case TAHQ_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case TAHQ_ERR_MISALIGNED: return "device pointer not 16-byte aligned";
     case TAHQ_ERR_HIP: return "kernel launch failed";
+    case TAHQ_ERR_TOO_LARGE: return "configuration needs more scratch than the built-in buffer of tahq_encode_noalloc holds";
     }
     return "unknown status";
 }
