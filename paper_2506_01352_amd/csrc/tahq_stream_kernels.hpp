@@ -471,22 +471,64 @@ __device__ __forceinline__ void load_meta(const uint8_t *__restrict__ packed, co
     m.rank0 = ranks[j0 >> 6];
 }
 
+// Number of set bits of `mask` in the lanes below mine (two instructions).
+__device__ __forceinline__ uint32_t bits_below_me(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
 // Width of my tile (LOW or LOW + 1 bits), its payload position inside the batch (in units of G/8 bytes), and
-// the number of wide tiles in the batch.
+// the number of wide tiles in the batch.  A wavefront's 64 tiles are one bit map word.
 template <int TILES, int LOW>
 __device__ __forceinline__ void tile_pos(const BatchMeta<TILES> &m, int tid, uint32_t *b, uint32_t *rel, uint32_t *total4)
 {
-    uint32_t bb = LOW, rr = 0, tot = 0;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6);      // the same in every lane
+    const uint32_t lane = (uint32_t)tid & 63u;
+    uint64_t mine = 0;
+    uint32_t before = 0, tot = 0;
 #pragma unroll
     for (int w = 0; w < BatchMeta<TILES>::WORDS; ++w) {
-        if (w == (tid >> 6)) {
-            const uint32_t bit = (uint32_t)tid & 63u;
-            bb = (uint32_t)LOW + (uint32_t)((m.word[w] >> bit) & 1ull);
-            rr = (uint32_t)LOW * (uint32_t)tid + tot + (uint32_t)__popcll(m.word[w] & ((1ull << bit) - 1ull));
-        }
+        if ((uint32_t)w == wave) { mine = m.word[w]; before = tot; }
         tot += (uint32_t)__popcll(m.word[w]);
     }
-    *b = bb; *rel = rr; *total4 = tot;
+    const uint32_t half = lane < 32u ? (uint32_t)mine : (uint32_t)(mine >> 32);
+    *b = (uint32_t)LOW + ((half >> (lane & 31u)) & 1u);
+    *rel = (uint32_t)LOW * (uint32_t)tid + before + bits_below_me(mine);
+    *total4 = tot;
+}
+
+// Tiles of a batch regrouped by class (0..3; anything else sorts nowhere): the position of my tile when the batch is
+// ordered by class and, inside a class, by tile index.  Two steps with a workgroup barrier between them.
+// Step 1: my rank among the tiles of my class in my wavefront; lane 0 leaves the wavefront's four counts in
+// `counts` (LDS, uint32[4 * WAVES], class-major).
+template <int WAVES>
+__device__ __forceinline__ uint32_t class_rank_in_wave(uint32_t cls, uint32_t wave, uint32_t lane, uint32_t *counts)
+{
+    uint32_t rank = 0;
+#pragma unroll
+    for (uint32_t c = 0; c < 4; ++c) {
+        const uint64_t m = __ballot(cls == c);
+        if (cls == c) rank = bits_below_me(m);
+        if (lane == 0) counts[c * WAVES + wave] = (uint32_t)__popcll(m);
+    }
+    return rank;
+}
+
+// Step 2 (after the barrier): tiles that come before my class-and-wavefront group.  In class-major order that is
+// the exclusive prefix sum of the 4 * WAVES counts: lanes 0 .. 4 WAVES - 1 scan them with row shifts, and every
+// lane fetches the entry of its own group.  All lanes of the wavefront must be enabled.
+template <int WAVES>
+__device__ __forceinline__ uint32_t class_group_base(uint32_t cls, uint32_t wave, uint32_t lane, const uint32_t *counts)
+{
+    static_assert(4 * WAVES <= 16, "the counts must fit one row of 16 lanes");
+    const uint32_t own = lane < 4u * WAVES ? counts[lane] : 0u;
+    uint32_t v = own;
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);     // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);     // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);     // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);     // row_shr:8
+    const uint32_t group = cls < 4u ? cls * WAVES + wave : 0u;
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(group << 2), (int)(v - own));
 }
 
 // Three-input float min / max in one instruction each (no NaN canonicalisation around them).
@@ -669,9 +711,9 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
     __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == WIDE) << 8 | rel << 9
     __shared__ uint16_t order[B::TILES];         // tiles in class order
-    __shared__ uint32_t class_count[WAVES][4];
+    __shared__ uint32_t class_count[4 * WAVES];  // tiles per class and wavefront, class-major
     U *pay = reinterpret_cast<U *>(lds);         // valid only after every lane has left the rows
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
     const uint32_t left = (uint32_t)(T - j0);
     const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
@@ -696,22 +738,11 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
         info[tid] = pv | ((b == WIDE) ? 0x100u : 0u) | (rel << 9);
         cls = ((pv >> 7) << 1) | (b == WIDE ? 1u : 0u);
     }
-    uint32_t rank_in_wave = 0;
-#pragma unroll
-    for (uint32_t c = 0; c < 4; ++c) {
-        const uint64_t m = __ballot(cls == c);
-        if (cls == c) rank_in_wave = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (lane == 0) class_count[wave][c] = (uint32_t)__popcll(m);
-    }
+    const uint32_t rank_in_wave = class_rank_in_wave<WAVES>(cls, (uint32_t)wave, (uint32_t)lane, class_count);
     __syncthreads();
-    if (valid) {
-        uint32_t pos = rank_in_wave;
-#pragma unroll
-        for (uint32_t c = 0; c < 4; ++c)
-#pragma unroll
-            for (int w = 0; w < WAVES; ++w)
-                if (c < cls || (c == cls && w < wave)) pos += class_count[w][c];
-        order[pos] = (uint16_t)tid;
+    {
+        const uint32_t pos = rank_in_wave + class_group_base<WAVES>(cls, (uint32_t)wave, (uint32_t)lane, class_count);
+        if (valid) order[pos] = (uint16_t)tid;
     }
     __syncthreads();
 
@@ -878,8 +909,8 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
     constexpr int WAVES = (B::TILES + 63) / 64;
     __shared__ uint2 tile_meta[B::TILES];        // per tile: scale | zero << 16, pivot byte | (b == WIDE) << 8 | rel << 9
     __shared__ uint16_t order[B::TILES];         // tiles in class order
-    __shared__ uint32_t class_count[WAVES][4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ uint32_t class_count[4 * WAVES];  // tiles per class and wavefront, class-major
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
     const uint32_t per = (nfull + gridDim.x - 1) / gridDim.x;
     const uint32_t first = blockIdx.x * per;
@@ -945,24 +976,10 @@ void k_decode(const uint8_t *__restrict__ packed, void *__restrict__ out, Layout
         // the p-th tile in class order, so the butterfly runs only in the wavefronts that hold transformed tiles.
         tile_meta[tid] = make_uint2(s16 | (z16 << 16), pv | ((b == WIDE) ? 0x100u : 0u) | (rel << 9));
         const uint32_t cls = ((pv >> 7) << 1) | (b == WIDE ? 1u : 0u);
-        uint32_t rank_in_wave = 0;
-#pragma unroll
-        for (uint32_t c = 0; c < 4; ++c) {
-            const uint64_t mask = __ballot(cls == c);
-            if (cls == c) rank_in_wave = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-            if (lane == 0) class_count[wave][c] = (uint32_t)__popcll(mask);
-        }
+        const uint32_t rank_in_wave = class_rank_in_wave<WAVES>(cls, (uint32_t)wave, (uint32_t)lane, class_count);
         __syncthreads();
         if (have_prev) stage_out<G, ES, true>(out, (uint64_t)prev_batch * B::TILES, B::TILES, lds);
-        {
-            uint32_t pos = rank_in_wave;
-#pragma unroll
-            for (uint32_t c = 0; c < 4; ++c)
-#pragma unroll
-                for (int w = 0; w < WAVES; ++w)
-                    if (c < cls || (c == cls && w < wave)) pos += class_count[w][c];
-            order[pos] = (uint16_t)tid;
-        }
+        order[rank_in_wave + class_group_base<WAVES>(cls, (uint32_t)wave, (uint32_t)lane, class_count)] = (uint16_t)tid;
         __syncthreads();
 
         if (batch + 1 < last) {
