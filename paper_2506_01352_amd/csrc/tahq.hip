@@ -67,16 +67,17 @@ inline uint32_t resident_blocks(const void *kernel, int threads)
 
 template <int G, bool BF16>
 struct LaunchEntropy {
-    // hist0 != nullptr: also build the selection's first-digit histogram (units must be whole batches)
-    static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, uint32_t *hist0,
-                    uint64_t n_per_unit, hipStream_t st)
+    // hist != nullptr: also build the selection's first histogram, `bins` bins per ranking unit (units must be whole
+    // batches): the keys' first radix digit if bin_scale == 0, the entropies' linear bins otherwise
+    static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, uint32_t *hist,
+                    uint32_t bins, float bin_scale, uint64_t n_per_unit, hipStream_t st)
     {
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
         static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_entropy<G, BF16>), B::TILES);
-        const uint32_t unit_batches = hist0 ? (uint32_t)(n_per_unit / B::TILES) : 1u;
+        const uint32_t unit_batches = hist ? (uint32_t)(n_per_unit / B::TILES) : 1u;
         hipLaunchKernelGGL((k_entropy<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, d_in, d_H, T,
-                           eps_l1, eps_log, hist0, unit_batches, kDigit0Bins);
+                           eps_l1, eps_log, hist, unit_batches, bins, bin_scale);
     }
     static bool can_fuse_histogram(uint64_t n_per_unit) { return n_per_unit % Batch<G, BF16 ? 2 : 4>::TILES == 0; }
 };
@@ -150,15 +151,13 @@ struct LaunchAllocEntropy {
     }
 };
 
-// Returns true if the first-digit histogram was built along the way.
-bool launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, uint32_t *hist0,
-                    hipStream_t st)
+// Entropy of every quantization tile; with `hist`, also the selection's first histogram (the caller has checked
+// that the ranking units are whole batches).
+void launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, uint32_t *hist, uint32_t bins,
+                    float bin_scale, hipStream_t st)
 {
-    bool fuse = false;
-    if (hist0) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fuse);
-    dispatch<LaunchEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_H, (uint32_t)s.T, cfg->eps_l1, cfg->eps_log,
-                            fuse ? hist0 : (uint32_t *)nullptr, s.n, st);
-    return fuse;
+    dispatch<LaunchEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_H, (uint32_t)s.T, cfg->eps_l1, cfg->eps_log, hist, bins,
+                            bin_scale, s.n, st);
 }
 
 // ---- backward-pass fixed-point compressor
@@ -261,7 +260,7 @@ tahq_status tahq_tile_entropy(const tahq_config *cfg, const void *d_in, float *d
     if (rc != TAHQ_OK) return rc;
     if (!d_in || !d_entropy) return TAHQ_ERR_NULL;
     if (misaligned(d_in) || misaligned(d_entropy)) return TAHQ_ERR_MISALIGNED;
-    launch_entropy(s, cfg, d_in, d_entropy, nullptr, (hipStream_t)stream);
+    launch_entropy(s, cfg, d_in, d_entropy, nullptr, 0u, 0.0f, (hipStream_t)stream);
     return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
 }
 
@@ -274,7 +273,7 @@ tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, fl
     if (!d_in || !d_entropy) return TAHQ_ERR_NULL;
     if (misaligned(d_in) || misaligned(d_entropy)) return TAHQ_ERR_MISALIGNED;
     if (s.m == 1) {
-        launch_entropy(s, cfg, d_in, d_entropy, nullptr, (hipStream_t)stream);
+        launch_entropy(s, cfg, d_in, d_entropy, nullptr, 0u, 0.0f, (hipStream_t)stream);
     } else {
         if (!d_workspace) return TAHQ_ERR_NULL;
         Workspace ws;
@@ -352,17 +351,38 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
         uint32_t *state = reinterpret_cast<uint32_t *>(wsb + ws.state);
         uint32_t *seg = reinterpret_cast<uint32_t *>(wsb + ws.seg);
         uint8_t *sel = wsb + ws.sel;
-        // the entropy kernel builds the first-digit histogram itself when units are whole batches
-        bool fused = false;
-        if (!wide && !small_units) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &fused);
+        // the entropy kernel builds the selection's first histogram itself when units are whole batches
+        bool whole_batches = false;
+        if (!wide && !small_units) dispatch<CanFuse>(s.G, s.dtype == TAHQ_BF16, s.n, &whole_batches);
+        // Large units that start on 64-tile boundaries are ranked in one launch from a histogram of linear bins;
+        // everything else (and every unit when the caller forces it) by the multi-launch radix select.
+        const bool fused_select = whole_batches && !multi_launch && s.n % 64 == 0;
+        const bool fused = whole_batches && !fused_select;       // first radix digit folded into the entropy kernel
+        uint32_t *lin_hist = reinterpret_cast<uint32_t *>(wsb + ws.lin_hist);
+        // bins of width ln(A) / kLinBins: the entropy of A channels lies in [0, ln A]
+        const float bin_scale = (float)((double)kLinBins / __builtin_log((double)s.A));
         if (phases & TAHQ_PHASE_ENTROPY) {
             if (wide)
                 dispatch<LaunchAllocEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, H, reinterpret_cast<float *>(wsb + ws.part),
                                              reinterpret_cast<float *>(wsb + ws.inv_norm), (uint32_t)s.T, s.m,
                                              cfg->eps_l1, cfg->eps_log, st);
+            else if (fused_select)
+                launch_entropy(s, cfg, d_in, H, lin_hist, kLinBins, bin_scale, st);
             else
-                launch_entropy(s, cfg, d_in, H, small_units ? (uint32_t *)nullptr : hist0, st);
+                launch_entropy(s, cfg, d_in, H, fused ? hist0 : (uint32_t *)nullptr, kDigit0Bins, 0.0f, st);
         }
+        if ((phases & TAHQ_PHASE_SELECT) && fused_select) {
+            const dim3 grid((uint32_t)((s.n + kFusedKeysPerBlock - 1) / kFusedKeysPerBlock), s.U);
+            uint32_t *fused_state = reinterpret_cast<uint32_t *>(wsb + ws.fused);
+            uint2 *cand = reinterpret_cast<uint2 *>(wsb + ws.cand);
+            uint32_t *block_above = reinterpret_cast<uint32_t *>(wsb + ws.block_above);
+            hipLaunchKernelGGL(k_select_classify, grid, dim3(kFusedThreads), 0, st, (const float *)H, (uint32_t)s.n,
+                               (uint32_t)s.k, bin_scale, (const uint32_t *)lin_hist, fused_state, cand, block_above,
+                               bitmap);
+            hipLaunchKernelGGL(k_select_resolve, grid, dim3(kFusedThreads), 0, st, (const float *)H, (uint32_t)s.n,
+                               (uint32_t)s.k, bin_scale, (const uint32_t *)lin_hist, (const uint32_t *)fused_state,
+                               (const uint2 *)cand, (const uint32_t *)block_above, bitmap, ranks);
+        } else
         if ((phases & TAHQ_PHASE_SELECT) && small_units) {
             const uint32_t n32 = (uint32_t)s.nA, k32 = (uint32_t)s.kA;
             const int aligned = (!wide && s.n % 64 == 0) ? 1 : 0;

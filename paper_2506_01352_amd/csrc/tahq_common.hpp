@@ -32,15 +32,21 @@ constexpr uint32_t kSegTiles = 1024;     // tiles one wavefront handles in the s
 constexpr uint32_t kHistBins = 2048;      // bins of radix digits 1 and 2 (11 bits each)
 constexpr uint32_t kDigit0Bins = 1024;    // bins of radix digit 0 (key bits 31..22)
 constexpr uint32_t kRadixKeysPerBlock = 8192;
+constexpr uint32_t kLinBins = 2048;       // bins of the entropy histogram of the single-launch selection of large units
+constexpr uint32_t kCandCap = 16384;      // tiles of the threshold bin that the selection keeps in a list, per ranking unit
 
 struct Workspace {
     // offsets in bytes from the workspace base
     uint64_t hist0;      // uint32[U][kDigit0Bins]: first-digit histogram      (zeroed per call)
     uint64_t coarse;     // uint32[U][2][64]: super-bin totals of digits 1, 2   (zeroed per call)
     uint64_t state;      // uint32[U][8] selection state
+    uint64_t lin_hist;   // uint32[U][kLinBins]: entropies by linear bin                  (zeroed per call)
+    uint64_t fused;      // uint32[U][4]: candidates listed, workgroups done              (zeroed per call)
     uint64_t zero_bytes; // bytes from `hist0` that must be zero before the selection starts
     uint64_t partial;    // uint32[U][2][hb][kHistBins]: per-workgroup histograms of digits 1, 2
     uint64_t keys;       // float[T] entropies
+    uint64_t cand;       // uint2[U][kCandCap]: (key, tile) of the tiles in the threshold bin
+    uint64_t block_above; // uint32[U][ceil(n / 16384)]: tiles above the threshold bin, per block of 16384 tiles
     uint64_t seg;        // uint32[U][nseg][2]: keys equal to / above the threshold, per segment
     uint64_t sel;        // uint8[T] (only when n % 64 != 0, or A > G)
     uint64_t part;       // float[T]: per-quantization-tile partial sums            (only when A > G)
@@ -110,9 +116,13 @@ void make_workspace(const Shape &s, Workspace *w)
     w->hist0 = off;  off += (uint64_t)s.U * kDigit0Bins * 4;
     w->coarse = off; off += (uint64_t)s.U * 2 * 64 * 4;
     w->state = off;  off += (uint64_t)s.U * 8 * 4;
+    w->lin_hist = off; off += (uint64_t)s.U * kLinBins * 4;
+    w->fused = off;  off += (uint64_t)s.U * 4 * 4;
     w->zero_bytes = off;
     off = pad256(off);
     w->partial = off; off = pad256(off + (uint64_t)s.U * 2 * w->hb * kHistBins * 4);
+    w->cand = off;  off = pad256(off + (uint64_t)s.U * kCandCap * 8);
+    w->block_above = off; off = pad256(off + (uint64_t)s.U * ((s.nA + 16383) / 16384) * 4);
     w->keys = off;  off = pad256(off + s.T * 4);
     w->seg = off;   off = pad256(off + (uint64_t)s.U * w->nseg * 8);
     w->sel = off;   off = pad256(off + s.T);
@@ -143,6 +153,20 @@ __device__ __forceinline__ float log_contract(float u)
     P = __builtin_fmaf(P, m, 0x1.c4859ep+2f);
     P = __builtin_fmaf(P, m, -0x1.5165a2p+1f);
     return __builtin_fmaf((float)e, kLn2, P);
+}
+
+// Order-preserving 32-bit key of an entropy (larger entropy -> larger key).
+__device__ __forceinline__ uint32_t order_key(float h)
+{
+    const uint32_t u = __float_as_uint(h);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Linear bin of an entropy, 0 .. kLinBins - 1: non-decreasing in the entropy (so a higher bin means a higher rank),
+// and the same instruction sequence wherever it is evaluated.  Negative values and NaN go to bin 0.
+__device__ __forceinline__ uint32_t linear_bin(float h, float scale)
+{
+    return (uint32_t)__builtin_amdgcn_fmed3f(h * scale, 0.0f, (float)(kLinBins - 1));
 }
 
 // fp32(1/sqrt(G)), the normalisation of Eq. 4.

@@ -573,6 +573,368 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     }
 }
 
+// ---- large ranking units: the selection in two launches after the entropy kernel
+//
+// The entropy kernel leaves, per ranking unit, a histogram of the entropies over kLinBins linear bins.  The bin of an
+// entropy is non-decreasing in it, so the k-th largest entropy lies in the bin b* where the counts, summed from the
+// top, reach k: every tile in a higher bin is selected, every tile in a lower bin is not, and only the tiles IN
+// bin b* (about one in a few hundred for activations) need an exact ranking for the `rem` places that are left.
+//
+//   k_select_classify (workgroups of 1024 threads over blocks of 16384 tiles): find b*; write the bit map words with
+//     the tiles above b* and the block's count of them; append (key, tile) of the tiles in b* to the unit's
+//     candidate list.
+//   k_select_resolve (same grid): every workgroup ranks the unit's candidates exactly for itself -- radix select on
+//     the keys, then, among the keys equal to the threshold, by tile index, so that ties go to the lower index
+//     whatever order the list came in -- adds the selected candidates of its own block to the block's bit map
+//     words, and writes the block's part of the rank table (tiles above b* in the blocks before it, from the
+//     counts; selected candidates before it, counted while ranking).  Ranking a few thousand candidates sixteen to
+//     thirty-two times over costs less than one workgroup walking the unit's whole bit map.
+// If a unit's bin b* holds more tiles than the list does (massive ties), the unit's first workgroup of the second
+// kernel does all of it alone, straight from the entropies: slower but as exact.  Needs ranking units that start on
+// 64-tile boundaries.
+// (One launch, with the last workgroup of every unit doing the second part, measured ten times slower: what a
+// workgroup wrote becomes visible to a workgroup on another XCD only through fences that write back the L2.)
+
+constexpr uint32_t kFusedThreads = 1024;
+constexpr uint32_t kFusedKeysPerBlock = 16 * kFusedThreads;
+
+// Workgroup-wide radix select over the values that `each` hands to its argument (every thread visits its own share
+// of the values; each(g) calls g(value) for each of them): the `want`-th largest value (1 <= want <= number of values)
+// and how many values equal to it belong to the `want` largest.  The values of one selection lie close together
+// (the keys of one histogram bin), so the digits are taken from value - minimum: 12 bits at a time from the top of
+// max - min, usually two passes.  Called by all 1024 threads; `copies` (uint32[8192]), `lh` (uint32[4096 + 64]) and
+// `chosen` (uint32[4]) are LDS scratch; the result is the same in every thread.
+template <class Each>
+__device__ __forceinline__ void block_radix_select(uint32_t want, Each each, uint32_t *copies, uint32_t *lh,
+                                                   uint32_t *chosen, uint32_t *thr_out, uint32_t *take_out)
+{
+    constexpr int kBins = 4096;
+    const int tid = threadIdx.x, lane = tid & 63;
+    if (tid == 0) { chosen[2] = 0xffffffffu; chosen[3] = 0u; }
+    __syncthreads();
+    {
+        uint32_t lo = 0xffffffffu, hi = 0u;
+        each([&](uint32_t val) { lo = val < lo ? val : lo; hi = val > hi ? val : hi; });
+        // per wavefront first: a thousand atomics on one LDS address would take longer than the rest of the selection
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, off, 64), ohi = (uint32_t)__shfl_xor((int)hi, off, 64);
+            lo = olo < lo ? olo : lo;
+            hi = ohi > hi ? ohi : hi;
+        }
+        if (lane == 0 && lo <= hi) { atomicMin(&chosen[2], lo); atomicMax(&chosen[3], hi); }
+    }
+    __syncthreads();
+    const uint32_t vmin = chosen[2], span = chosen[3] - vmin;
+    int bits = 32 - __builtin_clz(span | 1u);    // digits cover bits [0, bits) of value - vmin
+    uint32_t prefix = 0;                         // the digits found so far, as the top bits of value - vmin
+    // two copies of every bin, indexed by the lane: a wavefront's atomics on one LDS address are serialized
+    const uint32_t my_copy = (uint32_t)lane & 1u;
+#pragma unroll 1
+    while (true) {
+        const int shift = bits > 12 ? bits - 12 : 0;         // this pass: bits [shift, bits)
+        const uint32_t mask = (1u << (bits - shift)) - 1u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) copies[i * (int)kFusedThreads + tid] = 0;
+        __syncthreads();
+        each([&](uint32_t val) {
+            const uint32_t d = val - vmin;
+            if (bits == 32 || (d >> bits) == prefix) atomicAdd(&copies[(((d >> shift) & mask) << 1) | my_copy], 1u);
+        });
+        __syncthreads();
+#pragma unroll
+        for (int part = 0; part < kBins / (int)kFusedThreads; ++part) {
+            const uint32_t bin = (uint32_t)tid + kFusedThreads * part;
+            lh[bin + (bin >> 6)] = bin <= mask ? copies[2 * bin] + copies[2 * bin + 1] : 0u;
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t cs = 0;                                                // lane l: chunk 63 - l of 64 bins, from the top
+#pragma unroll 16
+            for (int i = 0; i < 64; ++i) cs += lh[(63 - lane) * 65 + i];
+            const uint32_t above = wave_incl_scan(cs) - cs;
+            const uint64_t who = __ballot(above < want && want <= above + cs);
+            const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
+            const uint32_t chunk = 63u - (uint32_t)src;
+            const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
+            const uint32_t bs = lh[chunk * 65 + (63 - lane)];
+            const uint32_t above2 = wave_incl_scan(bs) - bs;
+            const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
+            const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
+            if (lane == src2) { chosen[0] = chunk * 64 + (63u - (uint32_t)src2); chosen[1] = want2 - above2; }
+        }
+        __syncthreads();
+        prefix = (bits - shift == 32) ? chosen[0] : ((prefix << (bits - shift)) | chosen[0]);
+        want = chosen[1];
+        __syncthreads();
+        if (shift == 0) break;
+        bits = shift;
+    }
+    *thr_out = vmin + prefix;
+    *take_out = want;
+}
+
+__global__ __launch_bounds__(kFusedThreads) void k_select_classify(const float *__restrict__ H, uint32_t n, uint32_t k,
+                                                                   float bin_scale,
+                                                                   const uint32_t *__restrict__ lin_hist,
+                                                                   uint32_t *__restrict__ fused,
+                                                                   uint2 *__restrict__ cand,
+                                                                   uint32_t *__restrict__ block_above,
+                                                                   uint64_t *__restrict__ bitmap)
+{
+    constexpr int KPT = 16;                      // keys per thread: wavefront w owns 16 groups of 64 tiles
+    __shared__ uint32_t chosen[2];
+    __shared__ uint32_t wave_cand[kFusedThreads / 64], wave_above[kFusedThreads / 64];
+    const uint32_t u = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const float *uH = H + (uint64_t)u * n;
+    uint32_t *listed = fused + (uint64_t)u * 4;              // candidates listed so far
+    uint2 *ucand = cand + (uint64_t)u * kCandCap;
+    uint64_t *ubitmap = bitmap + (((uint64_t)u * n) >> 6);   // units start on 64-tile boundaries
+    const uint32_t ngroups = n >> 6;
+
+    // all loads first (from a clamped index: none of them sits behind a branch)
+    const uint32_t group0 = blockIdx.x * (kFusedKeysPerBlock / 64) + (uint32_t)(KPT * wave);
+    float h[KPT];
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+        const uint32_t i = (group0 + r) * 64u + lane;
+        h[r] = uH[i < n ? i : n - 1];
+    }
+    if (tid < 64) {
+        uint32_t bin, rem;
+        pick_bin<kLinBins>(lin_hist + (uint64_t)u * kLinBins, k, &bin, &rem);
+        if (lane == 0) { chosen[0] = bin; chosen[1] = rem; }
+    }
+    __syncthreads();
+    const uint32_t bstar = chosen[0];
+
+    uint32_t bins[KPT];
+    uint64_t my_word = 0;
+    uint32_t n_cand = 0, n_above = 0;            // of my wavefront (the same in every lane)
+#pragma unroll
+    for (int r = 0; r < KPT; ++r) {
+        const bool ok = (group0 + r) * 64u + lane < n;
+        bins[r] = ok ? linear_bin(h[r], bin_scale) : 0xffffffffu;
+        const uint64_t above = __ballot(ok && bins[r] > bstar);
+        if (lane == r) my_word = above;
+        n_above += (uint32_t)__popcll(above);
+        n_cand += (uint32_t)__popcll(__ballot(bins[r] == bstar));
+    }
+    if (lane < KPT && group0 + lane < ngroups) ubitmap[group0 + lane] = my_word;
+    // one place in the list for the whole workgroup (a unit's workgroups all add to one counter: few, large additions)
+    if (lane == 0) { wave_cand[wave] = n_cand; wave_above[wave] = n_above; }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t total = 0, above = 0;
+        for (int w = 0; w < (int)(kFusedThreads / 64); ++w) { total += wave_cand[w]; above += wave_above[w]; }
+        chosen[1] = total ? atomicAdd(listed, total) : 0u;
+        block_above[(uint64_t)u * gridDim.x + blockIdx.x] = above;
+    }
+    __syncthreads();
+    if (n_cand != 0) {
+        uint32_t base = chosen[1];
+        for (int w = 0; w < wave; ++w) base += wave_cand[w];
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const uint64_t m = __ballot(bins[r] == bstar);
+            if (bins[r] == bstar) {
+                const uint32_t pos = base + bits_below_me(m);
+                if (pos < kCandCap) ucand[pos] = make_uint2(order_key(h[r]), (group0 + r) * 64u + lane);
+            }
+            base += (uint32_t)__popcll(m);
+        }
+    }
+}
+
+// LDS of k_select_resolve
+struct ResolveLds {
+    uint32_t copies[8192];
+    uint32_t lh[4096 + 64];
+    uint32_t chosen[4];
+    uint32_t n_equal, n_before;
+    uint32_t equal_tile[kFusedThreads];          // tiles whose key equals the threshold (the first 1024)
+    uint32_t wave_total[kFusedThreads / 64];
+    uint32_t words[2 * (kFusedKeysPerBlock / 64)];           // the block's bit map words, as dwords
+};
+
+// Which of the candidates f visits are selected: `rem` of them, by (key descending, tile ascending).  each_candidate(f)
+// calls f(key, tile) for my share of the tiles in bin b*; take_it(tile) is called for every selected one.  All 1024
+// threads.
+template <class EachCandidate, class TakeIt>
+__device__ __forceinline__ void rank_candidates(uint32_t rem, EachCandidate each_candidate, TakeIt take_it, ResolveLds &L)
+{
+    const int tid = threadIdx.x;
+    if (tid == 0) L.n_equal = 0;
+    uint32_t thr, take;
+    block_radix_select(rem, [&](auto g) { each_candidate([&](uint32_t key, uint32_t) { g(key); }); }, L.copies, L.lh,
+                       L.chosen, &thr, &take);
+    // tiles above the threshold are taken; of those equal to it, the `take` with the lowest tile indices
+    each_candidate([&](uint32_t key, uint32_t tile) {
+        if (key > thr) take_it(tile);
+        else if (key == thr) {
+            const uint32_t at = atomicAdd(&L.n_equal, 1u);
+            if (at < kFusedThreads) L.equal_tile[at] = tile;
+        }
+    });
+    __syncthreads();
+    const uint32_t ne = L.n_equal;
+    if (ne <= kFusedThreads) {
+        // a handful, as a rule: thread t ranks the t-th of them among all of them
+        if ((uint32_t)tid < ne) {
+            const uint32_t mine = L.equal_tile[tid];
+            uint32_t lower = 0;
+            for (uint32_t i = 0; i < ne; ++i) lower += L.equal_tile[i] < mine ? 1u : 0u;
+            if (lower < take) take_it(mine);
+        }
+    } else {
+        uint32_t thr_index, unused;              // a tile with key == thr is taken iff ~tile >= thr_index
+        block_radix_select(take, [&](auto g) {
+            each_candidate([&](uint32_t key, uint32_t tile) { if (key == thr) g(~tile); });
+        }, L.copies, L.lh, L.chosen, &thr_index, &unused);
+        each_candidate([&](uint32_t key, uint32_t tile) { if (key == thr && ~tile >= thr_index) take_it(tile); });
+    }
+}
+
+// The overflow path: one workgroup resolves a whole unit from the entropies (bin b* holds more tiles than the list).
+__device__ __noinline__ void resolve_unit_alone(const float *__restrict__ uH, uint32_t n, uint32_t rank_base,
+                                                float bin_scale, uint32_t bstar, uint32_t rem,
+                                                uint64_t *__restrict__ ubitmap, uint32_t *__restrict__ uranks,
+                                                ResolveLds &L)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t ngroups = n >> 6;
+    uint32_t *ubits32 = reinterpret_cast<uint32_t *>(ubitmap);
+    if (rem != 0) {
+        rank_candidates(rem, [&](auto f) {
+            for (uint32_t i = tid; i < n; i += kFusedThreads) {
+                const float hv = uH[i];
+                if (linear_bin(hv, bin_scale) == bstar) f(order_key(hv), i);
+            }
+        }, [&](uint32_t tile) { atomicOr(&ubits32[tile >> 5], 1u << (tile & 31u)); }, L);
+    }
+    // every wavefront's atomics have been performed (acknowledged by the L2, where the loads below read) before
+    // anybody reads the words
+    __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
+    __syncthreads();
+    // the unit's rank table from the finished bit map (read where the atomics were performed, in the L2: this
+    // workgroup's L1 may hold older copies of some words); a thread takes eight consecutive groups per sweep
+    constexpr int GPT = 8;
+    uint32_t running = rank_base;
+    for (uint32_t g0 = 0; g0 < ngroups; g0 += GPT * kFusedThreads) {
+        const uint32_t first = g0 + (uint32_t)tid * GPT;
+        uint32_t c[GPT], mine = 0;
+#pragma unroll
+        for (int i = 0; i < GPT; ++i) {
+            const uint32_t g = first + i < ngroups ? first + i : ngroups - 1;      // clamped, masked below
+            const uint32_t lo = __hip_atomic_load(&ubits32[2 * g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t hi = __hip_atomic_load(&ubits32[2 * g + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            c[i] = first + i < ngroups ? (uint32_t)__popc(lo) + (uint32_t)__popc(hi) : 0u;
+            mine += c[i];
+        }
+        const uint32_t incl = wave_incl_scan(mine);
+        if (lane == 63) L.wave_total[wave] = incl;
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < (int)(kFusedThreads / 64); ++w) {
+            const uint32_t wt = L.wave_total[w];
+            if (w < wave) before += wt;
+            total += wt;
+        }
+        uint32_t rank = running + before + incl - mine;
+#pragma unroll
+        for (int i = 0; i < GPT; ++i) {
+            if (first + i < ngroups) uranks[first + i] = rank;
+            rank += c[i];
+        }
+        running += total;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kFusedThreads) void k_select_resolve(const float *__restrict__ H, uint32_t n, uint32_t k,
+                                                                  float bin_scale,
+                                                                  const uint32_t *__restrict__ lin_hist,
+                                                                  const uint32_t *__restrict__ fused,
+                                                                  const uint2 *__restrict__ cand,
+                                                                  const uint32_t *__restrict__ block_above,
+                                                                  uint64_t *__restrict__ bitmap,
+                                                                  uint32_t *__restrict__ ranks)
+{
+    __shared__ ResolveLds L;
+    constexpr uint32_t GROUPS = kFusedKeysPerBlock / 64;     // 64-tile groups of a block
+    const uint32_t u = blockIdx.y, blk = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const float *uH = H + (uint64_t)u * n;
+    const uint2 *ucand = cand + (uint64_t)u * kCandCap;
+    uint64_t *ubitmap = bitmap + (((uint64_t)u * n) >> 6);
+    uint32_t *uranks = ranks + (((uint64_t)u * n) >> 6);
+    const uint32_t ngroups = n >> 6;
+    const uint32_t group0 = blk * GROUPS;
+    const uint32_t mygroups = ngroups - group0 < GROUPS ? ngroups - group0 : GROUPS;
+
+    // everything this workgroup reads from global memory, requested at once: the candidates (sixteen per thread; the
+    // list always has room for them, what lies beyond its end is ignored), the block's words, the counts of the
+    // blocks before it, the histogram
+    constexpr int CPT = (int)(kCandCap / kFusedThreads);
+    uint2 c[CPT];
+#pragma unroll
+    for (int r = 0; r < CPT; ++r) c[r] = ucand[(uint32_t)r * kFusedThreads + tid];
+    const uint32_t listed = fused[(uint64_t)u * 4];
+    uint64_t my_word = 0;
+    if ((uint32_t)tid < mygroups) my_word = ubitmap[group0 + tid];
+    uint32_t above_before = 0;
+    for (uint32_t b = tid; b < blk; b += kFusedThreads) above_before += block_above[(uint64_t)u * gridDim.x + b];
+    if (tid < 64) {
+        uint32_t bin, rem;
+        pick_bin<kLinBins>(lin_hist + (uint64_t)u * kLinBins, k, &bin, &rem);
+        if (lane == 0) { L.chosen[0] = bin; L.chosen[1] = rem; }
+    }
+    if (tid == 0) L.n_before = 0;
+    if ((uint32_t)tid < GROUPS) { L.words[2 * tid] = (uint32_t)my_word; L.words[2 * tid + 1] = (uint32_t)(my_word >> 32); }
+    __syncthreads();
+    const uint32_t bstar = L.chosen[0], rem = L.chosen[1];
+    __syncthreads();                             // `chosen` is used again below
+
+    if (listed > kCandCap) {
+        if (blk == 0) resolve_unit_alone(uH, n, u * k, bin_scale, bstar, rem, ubitmap, uranks, L);
+        return;
+    }
+    // the selected candidates: those of my block go into its words, those before it are counted
+    const uint32_t first_tile = group0 * 64u;
+    uint32_t before = 0;
+    if (rem != 0) {
+        rank_candidates(rem, [&](auto f) {
+#pragma unroll
+            for (int r = 0; r < CPT; ++r)
+                if ((uint32_t)r * kFusedThreads + tid < listed) f(c[r].x, c[r].y);
+        }, [&](uint32_t tile) {
+            if (tile < first_tile) ++before;
+            else if (tile - first_tile < kFusedKeysPerBlock) atomicOr(&L.words[(tile - first_tile) >> 5], 1u << (tile & 31u));
+        }, L);
+    }
+    above_before += before;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) above_before += (uint32_t)__shfl_xor((int)above_before, off, 64);
+    if (lane == 0 && above_before != 0) atomicAdd(&L.n_before, above_before);
+    __syncthreads();
+    // the block's final words and rank-table entries: one group per thread of the first four wavefronts
+    uint32_t lo = 0, hi = 0;
+    if ((uint32_t)tid < GROUPS) { lo = L.words[2 * tid]; hi = L.words[2 * tid + 1]; }
+    const uint32_t cnt = (uint32_t)__popc(lo) + (uint32_t)__popc(hi);
+    const uint32_t incl = wave_incl_scan(cnt);
+    if (lane == 63) L.wave_total[wave] = incl;
+    __syncthreads();
+    if ((uint32_t)tid < mygroups) {
+        uint32_t rank = u * k + L.n_before + incl - cnt;     // every earlier unit holds exactly k wide tiles
+        for (int w = 0; w < wave; ++w) rank += L.wave_total[w];
+        ubitmap[group0 + tid] = ((uint64_t)hi << 32) | lo;
+        uranks[group0 + tid] = rank;
+    }
+}
+
 // Budget 3.0 or 4.0: every tile has the same width.
 __global__ __launch_bounds__(256) void k_bitmap_const(uint32_t T, int all4, uint64_t *__restrict__ bitmap,
                                                       uint32_t *__restrict__ ranks)

@@ -162,13 +162,6 @@ __device__ __forceinline__ float entropy_of_row(const uint8_t *row, float eps_l1
     return 0.0f - tree_sum<G>(a);
 }
 
-// Order-preserving 32-bit key of an entropy (larger entropy -> larger key).
-__device__ __forceinline__ uint32_t order_key(float h)
-{
-    const uint32_t u = __float_as_uint(h);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 constexpr int kDigit0Bits = 10;                  // first radix digit of the selection: key bits 31..22
 static_assert((1u << kDigit0Bits) == kDigit0Bins, "digit 0 width");
 
@@ -177,19 +170,21 @@ static_assert((1u << kDigit0Bits) == kDigit0Bins, "digit 0 width");
 // just before those loads, so that no wait for loads ever has a younger store in front of it.
 // The ragged last batch (T not a multiple of TILES) is handled after the loop by one workgroup.
 //
-// If `hist0` is given, the kernel also builds the first-digit histogram of the selection (Sec. 3.2,
-// top-p%): per ranking unit of `unit_batches` batches, counts of the keys' top 10 bits, accumulated in
-// LDS and flushed with global atomics when the workgroup moves to another unit and at its end.  This
-// needs units that are whole numbers of batches (the caller checks; otherwise it passes no histogram).
+// If `hist0` is given, the kernel also builds the first histogram of the selection (Sec. 3.2, top-p%): per
+// ranking unit of `unit_batches` batches, counts of the keys' top 10 bits (bin_scale == 0) or of the entropies'
+// linear bins (bin_scale > 0), `hist_stride` bins per unit, accumulated in LDS and flushed with global atomics
+// when the workgroup moves to another unit and at its end.  This needs units that are whole numbers of batches
+// (the caller checks; otherwise it passes no histogram).
 template <int G, bool BF16>
 __global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
 void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, float eps_l1, float eps_log,
-               uint32_t *__restrict__ hist0, uint32_t unit_batches, uint32_t hist_stride)
+               uint32_t *__restrict__ hist0, uint32_t unit_batches, uint32_t hist_stride, float bin_scale)
 {
     constexpr int ES = BF16 ? 2 : 4;
     using B = Batch<G, ES>;
     __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
-    __shared__ uint32_t lh[kDigit0Bins];
+    static_assert(kLinBins >= kDigit0Bins, "one LDS histogram serves both kinds of bins");
+    __shared__ uint32_t lh[kLinBins];
     const int tid = threadIdx.x;
     const uint32_t nfull = T / B::TILES, tail = T % B::TILES;
     const uint8_t *row = lds + tid * B::STRIDE;
@@ -198,11 +193,11 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
     const uint32_t last = first + per < nfull ? first + per : nfull;      // my batches: [first, last)
 
     if (hist0) {
-        for (int i = tid; i < (int)kDigit0Bins; i += B::TILES) lh[i] = 0;
+        for (int i = tid; i < (int)hist_stride; i += B::TILES) lh[i] = 0;
     }
     auto flush = [&](uint32_t unit) {
         __syncthreads();
-        for (int i = tid; i < (int)kDigit0Bins; i += B::TILES) {
+        for (int i = tid; i < (int)hist_stride; i += B::TILES) {
             const uint32_t c = lh[i];
             if (c) { atomicAdd(&hist0[(uint64_t)unit * hist_stride + i], c); lh[i] = 0; }
         }
@@ -230,7 +225,8 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
         if (have_prev) H[j_prev] = h_prev;
         if (batch + 1 < last) load_full(batch + 1);
         h_prev = entropy_of_row<G, BF16>(row, eps_l1, eps_log);
-        if (hist0) atomicAdd(&lh[order_key(h_prev) >> (32 - kDigit0Bits)], 1u);
+        if (hist0)
+            atomicAdd(&lh[bin_scale > 0.0f ? linear_bin(h_prev, bin_scale) : order_key(h_prev) >> (32 - kDigit0Bits)], 1u);
         j_prev = (uint64_t)batch * B::TILES + tid;
         have_prev = true;
         __syncthreads();

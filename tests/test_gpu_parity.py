@@ -193,6 +193,37 @@ def test_whole_tensor_ranking_scope(tahq):
     check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, 3.4, scope=1)
 
 
+def test_large_units_with_ties_at_the_threshold(tahq):
+    # Ranking units of 65536 and 49152 tiles take the two-launch selection of large units: a histogram of the
+    # entropies, then an exact ranking of the tiles in the threshold bin only.  (a) two kinds of token, all tiles of a
+    # token alike: the threshold bin holds half a unit, more than the candidate list takes, and thousands of equal
+    # entropies are split by tile index; (b) a fifth of the tiles share the highest entropy and the budget cuts that
+    # group in two: the list holds them all, the tie is resolved by a second selection on the index; (c) random
+    # tiles drawn from a pool of 3000, so that a few equal entropies meet at the threshold; (d) whole-tensor ranking.
+    rng = np.random.default_rng(21)
+    S, Cc, G = 512, 8192, 64
+    pat = rng.standard_normal((2, G)).astype(np.float32)
+    pat[1, 5] *= 30.0
+    kind = rng.integers(0, 2, size=(2, S))
+    xa = np.tile(pat[kind], (1, 1, Cc // G))
+    _say("[case] large units, massive ties: list overflow")
+    check_case(tahq, workloads.f32_to_bf16_bits(xa), 2, S, Cc, G, tahq.BF16, 3.25)
+    check_case(tahq, workloads.f32_to_bf16_bits(xa), 2, S, Cc, G, tahq.BF16, 3.75)
+
+    tiles = rng.standard_normal((2 * S * (Cc // G), G)).astype(np.float32)
+    flat = rng.random(tiles.shape[0]) < 0.2
+    tiles[flat] = np.where(rng.random((int(flat.sum()), G)) < 0.5, -1.5, 1.5).astype(np.float32)   # entropy ln G
+    _say("[case] large units, a fifth of the tiles tied at the top")
+    check_case(tahq, workloads.f32_to_bf16_bits(tiles), 2, S, Cc, G, tahq.BF16, 3.1)
+
+    pool = rng.standard_normal((3000, G)).astype(np.float32)
+    xc = pool[rng.integers(0, 3000, size=3 * 384 * (Cc // G))]
+    _say("[case] large units, tiles from a pool")
+    check_case(tahq, xc, 3, 384, Cc, G, tahq.F32, 3.4)
+    _say("[case] large units, whole-tensor ranking")
+    check_case(tahq, xc, 3, 384, Cc, G, tahq.F32, 3.6, scope=1)
+
+
 # Sec. 3.2 with allocation tiles of several quantization tiles, up to the whole token (A = C)
 WIDE = [
     (1, dict(), 128), (1, dict(), 512),
