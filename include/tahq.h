@@ -26,14 +26,18 @@
  * Conventions for every entry point
  *   - Pointers named d_* are DEVICE pointers (HIP global memory on the current
  *     device); `cfg` and all other pointers are HOST pointers.
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls, never synchronizes: it validates on the host, then
- *     only enqueues kernels on `stream`.
+ *   - The caller owns every buffer.  The library allocates nothing and never
+ *     synchronizes: it validates on the host, then only enqueues kernels on `stream`.
  *   - Device buffers must be 16-byte aligned and must not overlap.
  *   - Argument errors are returned before anything is enqueued.  Data-dependent
  *     conditions (NaN/Inf inputs, magnitudes beyond the binary16 range of the
  *     metadata, +-65504) are not detected: the result is defined but lossy.
- *   - A failed launch is reported as TAHQ_ERR_HIP (hipGetLastError is consumed).
+ *   - A failed launch is reported as TAHQ_ERR_HIP, and nothing is enqueued after it.  Every launch's
+ *     own status is used: an error that the caller's earlier HIP work left pending in the thread is
+ *     neither reported here nor cleared.
+ *   - The only thing the library remembers between calls is, per kernel and device, how many
+ *     workgroups of the kernel the device holds at once (a query of the runtime on first use; it is
+ *     not a stream operation and may happen while a stream is being captured).
  *
  * Stream layout (little-endian; every section padded to 64 bytes), T = number
  * of tiles = batch*seq*hidden/tile, k = wide (lo+1 bit) allocation tiles per ranking unit:
@@ -66,7 +70,8 @@ typedef enum {
     TAHQ_ERR_NULL = 1,                 /* a required pointer is NULL                     */
     TAHQ_ERR_INVALID_ARG = 2,          /* zero dimension, hidden % tile != 0, alloc_tile not a multiple of tile dividing hidden,
                                           budget outside [3,4] or NaN, bad enum */
-    TAHQ_ERR_UNSUPPORTED = 3,          /* tile not in {8, 16, 32, 64, 128}, or more than 2^31 tiles */
+    TAHQ_ERR_UNSUPPORTED = 3,          /* tile not in {8, 16, 32, 64, 128}, more than 2^31 tiles, or more than
+                                          65535 ranking units of more than 32768 tiles each */
     TAHQ_ERR_BUFFER_TOO_SMALL = 4,     /* packed capacity / packed_bytes below tahq_packed_size */
     TAHQ_ERR_WORKSPACE_TOO_SMALL = 5,  /* workspace capacity below tahq_workspace_size   */
     TAHQ_ERR_MISALIGNED = 6,           /* a device pointer is not 16-byte aligned        */
@@ -181,6 +186,30 @@ tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t pac
                         void *d_out, uint32_t out_dtype,
                         void *d_workspace, size_t workspace_capacity,
                         tahq_stream stream);
+
+/* Sample-wise use in a pipeline  [Alg. 1 steps 4-5: the sender ships Q(a) to the next stage, which
+ * de-quantizes on arrival; Sec. 3.4: the communication layer sees fixed-shape buffers].  With scope 0 every
+ * sample is ranked on its own, so a run of samples is a micro-batch of its own: tahq_encode_samples
+ * encodes samples [first, first + count) of the tensor at d_in into a SELF-CONTAINED stream -- byte for
+ * byte what tahq_encode writes for a tensor [count, seq, hidden] that holds just those samples, header
+ * included -- so that it can be sent while later samples are still being encoded (e.g. on another
+ * stream, with a workspace of its own), and tahq_decode_samples decodes such a stream into the same
+ * samples of the tensor at d_out as soon as it has arrived, whatever happens to the others.
+ *   cfg          the whole tensor's configuration (cfg->batch samples); scope must be 0
+ *   first, count the samples; first + count <= cfg->batch, count >= 1
+ *   d_in / d_out device: base of the WHOLE tensor [batch, seq, hidden]
+ *   d_packed     device: the run's stream, tahq_samples_packed_size(cfg, count) bytes
+ *   d_workspace  device scratch of tahq_samples_workspace_size(cfg, count) bytes; runs that may be in flight
+ *                at the same time need a workspace each
+ * Errors as tahq_encode / tahq_decode; TAHQ_ERR_INVALID_ARG for scope 1 or samples outside the tensor. */
+size_t tahq_samples_packed_size(const tahq_config *cfg, uint32_t count);
+size_t tahq_samples_workspace_size(const tahq_config *cfg, uint32_t count);
+tahq_status tahq_encode_samples(const tahq_config *cfg, uint32_t first, uint32_t count, const void *d_in,
+                                void *d_packed, size_t packed_capacity,
+                                void *d_workspace, size_t workspace_capacity, tahq_stream stream);
+tahq_status tahq_decode_samples(const tahq_config *cfg, uint32_t first, uint32_t count,
+                                const void *d_packed, size_t packed_bytes,
+                                void *d_out, uint32_t out_dtype, tahq_stream stream);
 
 /* Intermediates of the encoder, for tests and profiling  [Sec. 3.2 Eq. 1-2].
  *   d_entropy   device, written: float[T], the entropy of every raw quantization tile

@@ -355,8 +355,10 @@ static void analyse_tile(const tahq_oracle_cfg *c, const float *v, float *y, til
 
 /* The asymmetric uniform quantizer (the paper only cites it): min/max affine
  * with 2^b - 1 steps, real-valued zero-point = tile minimum, round half to even,
- * clamp.  Scale and zero-point travel as binary16, rounded outwards so that the
- * coded range always covers [mn, mx]. */
+ * clamp.  Scale and zero-point travel as binary16, rounded outwards (zero-point
+ * down, scale up), so that the coded range [z, z + L s] covers [mn, mx] up to the
+ * one binary32 rounding of (mx - z) / L: the top of the range may fall short of
+ * mx by a fraction 2^-22 of (mx - z), and the clamp takes care of that. */
 void tahq_oracle_quant_params(float mn, float mx, uint32_t b, uint16_t *s16, uint16_t *z16)
 {
     float Lv = (float)((1u << b) - 1u);

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     F32, BF16, TahqError, make_config, tahq_config,
     tahq_config_default, tahq_k_per_unit, tahq_packed_size, tahq_workspace_size,
     tahq_encode, tahq_encode_phases, tahq_decode, tahq_encode_noalloc, NOALLOC_MAX_WORKSPACE,
+    tahq_samples_packed_size, tahq_samples_workspace_size, tahq_encode_samples, tahq_decode_samples,
     PHASE_PROLOGUE, PHASE_ENTROPY, PHASE_SELECT, PHASE_QUANT, PHASE_ALL, SELECT_MULTI_LAUNCH,
     tahq_tile_entropy, tahq_alloc_tile_entropy, tahq_parse_header,
     tahq_status_string, tahq_version, library_path, Codec,

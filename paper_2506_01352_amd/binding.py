@@ -64,6 +64,16 @@ def _load():
     L.tahq_encode_phases.restype = C.c_int
     L.tahq_encode_phases.argtypes = [P, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32,
                                      C.c_void_p]
+    L.tahq_samples_packed_size.restype = C.c_size_t
+    L.tahq_samples_packed_size.argtypes = [P, C.c_uint32]
+    L.tahq_samples_workspace_size.restype = C.c_size_t
+    L.tahq_samples_workspace_size.argtypes = [P, C.c_uint32]
+    L.tahq_encode_samples.restype = C.c_int
+    L.tahq_encode_samples.argtypes = [P, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+    L.tahq_decode_samples.restype = C.c_int
+    L.tahq_decode_samples.argtypes = [P, C.c_uint32, C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint32,
+                                      C.c_void_p]
     L.tahq_decode.restype = C.c_int
     L.tahq_decode.argtypes = [P, C.c_void_p, C.c_size_t, C.c_void_p, C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tahq_tile_entropy.restype = C.c_int
@@ -141,6 +151,27 @@ def _nbytes(t):
     return 0 if t is None else t.numel() * t.element_size()
 
 
+_ESIZE = {F32: 4, BF16: 2}
+
+
+def _check_tensor(where, name, t, elements, dtype):
+    """The C ABI carries no capacity for the activation tensors: refuse, on the host, a tensor that is shorter than
+    batch*seq*hidden elements of `dtype`, or whose elements have another size (byte buffers are taken as they are)."""
+    if t is None or isinstance(t, int):
+        return
+    esize = _ESIZE.get(dtype)
+    if esize is None:
+        return                                   # the library rejects the dtype itself
+    if t.element_size() not in (1, esize):
+        raise ValueError(f"{where}: {name} has {t.element_size()}-byte elements, the configuration says {esize}")
+    if _nbytes(t) < elements * esize:
+        raise ValueError(f"{where}: {name} holds {_nbytes(t)} bytes, the configuration needs {elements * esize}")
+
+
+def _elements(cfg):
+    return cfg.batch * cfg.seq * cfg.hidden
+
+
 def _stream_handle(stream):
     if stream is None:
         import torch
@@ -154,6 +185,7 @@ def tahq_encode(cfg, d_in, d_packed, d_workspace, stream=None, packed_capacity=N
     """Enqueue the encoder.  All tensors are device tensors owned by the caller."""
     cap = _nbytes(d_packed) if packed_capacity is None else packed_capacity
     wcap = _nbytes(d_workspace) if workspace_capacity is None else workspace_capacity
+    _check_tensor("tahq_encode", "d_in", d_in, _elements(cfg), cfg.dtype)
     rc = _load().tahq_encode(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_packed), cap, _dev_ptr(d_workspace), wcap,
                              _stream_handle(stream))
     if rc != 0:
@@ -166,6 +198,7 @@ NOALLOC_MAX_WORKSPACE = 32 << 20     # TAHQ_NOALLOC_MAX_WORKSPACE of include/tah
 def tahq_encode_noalloc(cfg, d_in, d_packed, stream=None, packed_capacity=None):
     """tahq_encode on the library's built-in scratch: no workspace argument, nothing allocated."""
     cap = _nbytes(d_packed) if packed_capacity is None else packed_capacity
+    _check_tensor("tahq_encode_noalloc", "d_in", d_in, _elements(cfg), cfg.dtype)
     rc = _load().tahq_encode_noalloc(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_packed), cap, _stream_handle(stream))
     if rc != 0:
         raise TahqError(rc, "tahq_encode_noalloc")
@@ -176,6 +209,7 @@ SELECT_MULTI_LAUNCH = 16      # option bit for tahq_encode_phases: see include/t
 
 
 def tahq_encode_phases(cfg, d_in, d_packed, d_workspace, phases, stream=None):
+    _check_tensor("tahq_encode_phases", "d_in", d_in, _elements(cfg), cfg.dtype)
     rc = _load().tahq_encode_phases(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_packed), _nbytes(d_packed),
                                     _dev_ptr(d_workspace), _nbytes(d_workspace), phases, _stream_handle(stream))
     if rc != 0:
@@ -184,19 +218,51 @@ def tahq_encode_phases(cfg, d_in, d_packed, d_workspace, phases, stream=None):
 
 def tahq_decode(cfg, d_packed, d_out, out_dtype, stream=None, packed_bytes=None):
     nbytes = _nbytes(d_packed) if packed_bytes is None else packed_bytes
+    _check_tensor("tahq_decode", "d_out", d_out, _elements(cfg), out_dtype)
     rc = _load().tahq_decode(C.byref(cfg), _dev_ptr(d_packed), nbytes, _dev_ptr(d_out), out_dtype, None, 0,
                              _stream_handle(stream))
     if rc != 0:
         raise TahqError(rc, "tahq_decode")
 
 
+def tahq_samples_packed_size(cfg, count):
+    return int(_load().tahq_samples_packed_size(C.byref(cfg), count))
+
+
+def tahq_samples_workspace_size(cfg, count):
+    return int(_load().tahq_samples_workspace_size(C.byref(cfg), count))
+
+
+def tahq_encode_samples(cfg, first, count, d_in, d_packed, d_workspace, stream=None):
+    """Samples [first, first + count) of the whole tensor d_in -> a self-contained stream in d_packed."""
+    _check_tensor("tahq_encode_samples", "d_in", d_in, _elements(cfg), cfg.dtype)
+    rc = _load().tahq_encode_samples(C.byref(cfg), first, count, _dev_ptr(d_in), _dev_ptr(d_packed), _nbytes(d_packed),
+                                     _dev_ptr(d_workspace), _nbytes(d_workspace), _stream_handle(stream))
+    if rc != 0:
+        raise TahqError(rc, "tahq_encode_samples")
+
+
+def tahq_decode_samples(cfg, first, count, d_packed, d_out, out_dtype, stream=None):
+    """A stream of tahq_encode_samples -> samples [first, first + count) of the whole tensor d_out."""
+    _check_tensor("tahq_decode_samples", "d_out", d_out, _elements(cfg), out_dtype)
+    rc = _load().tahq_decode_samples(C.byref(cfg), first, count, _dev_ptr(d_packed), _nbytes(d_packed), _dev_ptr(d_out),
+                                     out_dtype, _stream_handle(stream))
+    if rc != 0:
+        raise TahqError(rc, "tahq_decode_samples")
+
+
 def tahq_tile_entropy(cfg, d_in, d_entropy, stream=None):
+    _check_tensor("tahq_tile_entropy", "d_in", d_in, _elements(cfg), cfg.dtype)
+    _check_tensor("tahq_tile_entropy", "d_entropy", d_entropy, _elements(cfg) // max(cfg.tile, 1), F32)
     rc = _load().tahq_tile_entropy(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_entropy), _stream_handle(stream))
     if rc != 0:
         raise TahqError(rc, "tahq_tile_entropy")
 
 
 def tahq_alloc_tile_entropy(cfg, d_in, d_entropy, d_workspace, stream=None):
+    _check_tensor("tahq_alloc_tile_entropy", "d_in", d_in, _elements(cfg), cfg.dtype)
+    _check_tensor("tahq_alloc_tile_entropy", "d_entropy", d_entropy,
+                  _elements(cfg) // max(cfg.alloc_tile or cfg.tile, 1), F32)
     rc = _load().tahq_alloc_tile_entropy(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_entropy), _dev_ptr(d_workspace),
                                          _nbytes(d_workspace), _stream_handle(stream))
     if rc != 0:
@@ -232,6 +298,7 @@ def tahq_naive_packed_size(cfg):
 
 def tahq_naive_encode(cfg, d_in, d_packed, stream=None, packed_capacity=None):
     cap = _nbytes(d_packed) if packed_capacity is None else packed_capacity
+    _check_tensor("tahq_naive_encode", "d_in", d_in, _elements(cfg), cfg.dtype)
     rc = _load().tahq_naive_encode(C.byref(cfg), _dev_ptr(d_in), _dev_ptr(d_packed), cap, _stream_handle(stream))
     if rc != 0:
         raise TahqError(rc, "tahq_naive_encode")
@@ -239,6 +306,7 @@ def tahq_naive_encode(cfg, d_in, d_packed, stream=None, packed_capacity=None):
 
 def tahq_naive_decode(cfg, d_packed, d_out, out_dtype, stream=None, packed_bytes=None):
     nbytes = _nbytes(d_packed) if packed_bytes is None else packed_bytes
+    _check_tensor("tahq_naive_decode", "d_out", d_out, _elements(cfg), out_dtype)
     rc = _load().tahq_naive_decode(C.byref(cfg), _dev_ptr(d_packed), nbytes, _dev_ptr(d_out), out_dtype,
                                    _stream_handle(stream))
     if rc != 0:

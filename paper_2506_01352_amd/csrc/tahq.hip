@@ -20,7 +20,10 @@
 #include "tahq_naive_kernels.hpp"
 #include "tahq_naive.h"
 
+#include <atomic>
 #include <mutex>
+#include <tuple>
+#include <utility>
 
 using namespace tahq;
 
@@ -53,16 +56,54 @@ inline void dispatch(uint32_t G, bool bf16, Args... args)
     else { if (bf16) F<128, true>::run(args...); else F<128, false>::run(args...); }
 }
 
+// Kernel launches of one call: each launch returns its own status (the thread's sticky "last error", which may
+// belong to the caller's earlier work, is neither read nor cleared), and after a failure nothing more is enqueued.
+struct Enqueue {
+    hipStream_t stream;
+    hipError_t status = hipSuccess;
+
+    template <typename... P, typename... A>
+    void operator()(void (*kernel)(P...), dim3 grid, dim3 block, A... args)
+    {
+        static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+        if (status != hipSuccess) return;
+        std::tuple<P...> values(static_cast<P>(args)...);
+        status = launch(kernel, grid, block, values, std::index_sequence_for<P...>{});
+    }
+    tahq_status result() const { return status == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP; }
+
+private:
+    template <typename... P, size_t... I>
+    hipError_t launch(void (*kernel)(P...), dim3 grid, dim3 block, std::tuple<P...> &values, std::index_sequence<I...>)
+    {
+        void *ptrs[] = {static_cast<void *>(&std::get<I>(values))...};
+        return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, stream);
+    }
+};
+
 // Grid of a persistent kernel: four times the workgroups that fit on the device at once (or fewer, if there
 // are fewer batches).  Every workgroup still pipelines a few batches, and the hardware dispatcher evens
 // out the load; a grid of exactly the resident count measured up to 30% slower.
-inline uint32_t resident_blocks(const void *kernel, int threads)
+// The resident count of a kernel is a property of the kernel and the device; it is looked up once per kernel and
+// device (a query of the runtime, no stream operation: also legal while a stream is being captured) and kept
+// in `cache`, one slot per device.
+struct ResidentCache { std::atomic<uint32_t> per_device[kMaxDevices]; };
+
+inline uint32_t resident_blocks(const void *kernel, int threads, ResidentCache &cache)
 {
-    int dev = 0, cus = 256, per_cu = 1;
-    if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) dev = 0;
+    const bool cached = dev < kMaxDevices;
+    if (cached) {
+        const uint32_t known = cache.per_device[dev].load(std::memory_order_relaxed);
+        if (known) return known;
+    }
+    int cus = 256, per_cu = 1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu <= 0) per_cu = 1;
-    return 4u * (uint32_t)cus * (uint32_t)per_cu;
+    const uint32_t res = 4u * (uint32_t)cus * (uint32_t)per_cu;
+    if (cached) cache.per_device[dev].store(res, std::memory_order_relaxed);
+    return res;
 }
 
 template <int G, bool BF16>
@@ -70,13 +111,15 @@ struct LaunchEntropy {
     // hist != nullptr: also build the selection's first histogram, `bins` bins per ranking unit (units must be whole
     // batches): the keys' first radix digit if bin_scale == 0, the entropies' linear bins otherwise
     static void run(const void *d_in, float *d_H, uint32_t T, float eps_l1, float eps_log, uint32_t *hist,
-                    uint32_t bins, float bin_scale, uint64_t n_per_unit, hipStream_t st)
+                    uint32_t bins, float bin_scale, uint64_t n_per_unit, Enqueue *qp)
     {
+        Enqueue &q = *qp;
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
-        static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_entropy<G, BF16>), B::TILES);
+        static ResidentCache cache;
+        const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_entropy<G, BF16>), B::TILES, cache);
         const uint32_t unit_batches = hist ? (uint32_t)(n_per_unit / B::TILES) : 1u;
-        hipLaunchKernelGGL((k_entropy<G, BF16>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, d_in, d_H, T,
+        q(k_entropy<G, BF16>, dim3(nb < res ? nb : res), dim3(B::TILES), d_in, d_H, T,
                            eps_l1, eps_log, hist, unit_batches, bins, bin_scale);
     }
     static bool can_fuse_histogram(uint64_t n_per_unit) { return n_per_unit % Batch<G, BF16 ? 2 : 4>::TILES == 0; }
@@ -91,37 +134,40 @@ struct CanFuse {
 template <int G, bool BF16>
 struct LaunchQuantPack {
     template <int LOW>
-    static void go(const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio, hipStream_t st)
+    static void go(const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio, Enqueue *qp)
     {
+        Enqueue &q = *qp;
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
-        hipLaunchKernelGGL((k_quant_pack<G, BF16, LOW>), dim3(nb), dim3(B::TILES), 0, st, d_in, packed, lay, T, tau,
+        q(k_quant_pack<G, BF16, LOW>, dim3(nb), dim3(B::TILES), d_in, packed, lay, T, tau,
                            eps_ratio);
     }
     static void run(uint32_t low, const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio,
-                    hipStream_t st)
+                    Enqueue *qp)
     {
-        if (low == 3u) go<3>(d_in, packed, lay, T, tau, eps_ratio, st);
-        else go<2>(d_in, packed, lay, T, tau, eps_ratio, st);
+        if (low == 3u) go<3>(d_in, packed, lay, T, tau, eps_ratio, qp);
+        else go<2>(d_in, packed, lay, T, tau, eps_ratio, qp);
     }
 };
 
 template <int G, bool BF16>
 struct LaunchDecode {
     template <int LOW>
-    static void go(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total_wide, hipStream_t st)
+    static void go(const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total_wide, Enqueue *qp)
     {
+        Enqueue &q = *qp;
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
-        static const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_decode<G, BF16, LOW>), B::TILES);
-        hipLaunchKernelGGL((k_decode<G, BF16, LOW>), dim3(nb < res ? nb : res), dim3(B::TILES), 0, st, packed, d_out, lay,
+        static ResidentCache cache;
+        const uint32_t res = resident_blocks(reinterpret_cast<const void *>(k_decode<G, BF16, LOW>), B::TILES, cache);
+        q(k_decode<G, BF16, LOW>, dim3(nb < res ? nb : res), dim3(B::TILES), packed, d_out, lay,
                            T, total_wide);
     }
     static void run(uint32_t low, const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total_wide,
-                    hipStream_t st)
+                    Enqueue *qp)
     {
-        if (low == 3u) go<3>(packed, d_out, lay, T, total_wide, st);
-        else go<2>(packed, d_out, lay, T, total_wide, st);
+        if (low == 3u) go<3>(packed, d_out, lay, T, total_wide, qp);
+        else go<2>(packed, d_out, lay, T, total_wide, qp);
     }
 };
 
@@ -130,23 +176,24 @@ struct LaunchAllocEntropy {
     // Entropies of allocation tiles of m > 1 quantization tiles: one pass if a workgroup's batch holds whole
     // allocation tiles, otherwise two streaming passes over the tensor.
     static void run(const void *d_in, float *d_H, float *part, float *inv_norm, uint32_t T, uint32_t m, float eps_l1,
-                    float eps_log, hipStream_t st)
+                    float eps_log, Enqueue *qp)
     {
+        Enqueue &q = *qp;
         using B = Batch<G, BF16 ? 2 : 4>;
         const uint32_t nb = (T + B::TILES - 1) / B::TILES;
         const uint32_t n_alloc = T / m;
         if (B::TILES % m == 0) {
-            hipLaunchKernelGGL((k_alloc_entropy<G, BF16>), dim3(nb), dim3(B::TILES), 0, st, d_in, d_H, T, m, eps_l1,
+            q(k_alloc_entropy<G, BF16>, dim3(nb), dim3(B::TILES), d_in, d_H, T, m, eps_l1,
                                eps_log);
             return;
         }
-        hipLaunchKernelGGL((k_tile_partial<G, BF16, false>), dim3(nb), dim3(B::TILES), 0, st, d_in,
+        q(k_tile_partial<G, BF16, false>, dim3(nb), dim3(B::TILES), d_in,
                            (const float *)nullptr, part, T, m, eps_log);
-        hipLaunchKernelGGL((k_alloc_reduce<false>), dim3(blocks_for(n_alloc)), dim3(256), 0, st, (const float *)part,
+        q(k_alloc_reduce<false>, dim3(blocks_for(n_alloc)), dim3(256), (const float *)part,
                            inv_norm, n_alloc, m, eps_l1);
-        hipLaunchKernelGGL((k_tile_partial<G, BF16, true>), dim3(nb), dim3(B::TILES), 0, st, d_in,
+        q(k_tile_partial<G, BF16, true>, dim3(nb), dim3(B::TILES), d_in,
                            (const float *)inv_norm, part, T, m, eps_log);
-        hipLaunchKernelGGL((k_alloc_reduce<true>), dim3(blocks_for(n_alloc)), dim3(256), 0, st, (const float *)part,
+        q(k_alloc_reduce<true>, dim3(blocks_for(n_alloc)), dim3(256), (const float *)part,
                            d_H, n_alloc, m, eps_l1);
     }
 };
@@ -154,10 +201,10 @@ struct LaunchAllocEntropy {
 // Entropy of every quantization tile; with `hist`, also the selection's first histogram (the caller has checked
 // that the ranking units are whole batches).
 void launch_entropy(const Shape &s, const tahq_config *cfg, const void *d_in, float *d_H, uint32_t *hist, uint32_t bins,
-                    float bin_scale, hipStream_t st)
+                    float bin_scale, Enqueue *qp)
 {
     dispatch<LaunchEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_H, (uint32_t)s.T, cfg->eps_l1, cfg->eps_log, hist, bins,
-                            bin_scale, s.n, st);
+                            bin_scale, s.n, qp);
 }
 
 // ---- backward-pass fixed-point compressor
@@ -188,20 +235,22 @@ tahq_status make_naive_shape(const tahq_naive_config *c, NaiveShape *s)
 
 template <int BITS>
 void launch_naive_encode(bool bf16, const void *d_in, uint8_t *packed, const NaiveHeader &hdr, uint32_t nchunks,
-                         float scale, hipStream_t st)
+                         float scale, Enqueue *qp)
 {
+    Enqueue &q = *qp;
     const dim3 grid((nchunks + kNaiveChunks - 1) / kNaiveChunks), block(kNaiveChunks);
-    if (bf16) hipLaunchKernelGGL((k_naive_encode<BITS, true>), grid, block, 0, st, d_in, packed, hdr, nchunks, scale);
-    else hipLaunchKernelGGL((k_naive_encode<BITS, false>), grid, block, 0, st, d_in, packed, hdr, nchunks, scale);
+    if (bf16) q(k_naive_encode<BITS, true>, grid, block, d_in, packed, hdr, nchunks, scale);
+    else q(k_naive_encode<BITS, false>, grid, block, d_in, packed, hdr, nchunks, scale);
 }
 
 template <int BITS>
 void launch_naive_decode(bool out_bf16, const uint8_t *packed, void *d_out, uint32_t nchunks, float inv_scale,
-                         hipStream_t st)
+                         Enqueue *qp)
 {
+    Enqueue &q = *qp;
     const dim3 grid((nchunks + kNaiveChunks - 1) / kNaiveChunks), block(kNaiveChunks);
-    if (out_bf16) hipLaunchKernelGGL((k_naive_decode<BITS, true>), grid, block, 0, st, packed, d_out, nchunks, inv_scale);
-    else hipLaunchKernelGGL((k_naive_decode<BITS, false>), grid, block, 0, st, packed, d_out, nchunks, inv_scale);
+    if (out_bf16) q(k_naive_decode<BITS, true>, grid, block, packed, d_out, nchunks, inv_scale);
+    else q(k_naive_decode<BITS, false>, grid, block, packed, d_out, nchunks, inv_scale);
 }
 
 // Every supported code width, for the switch over the run-time width.
@@ -260,8 +309,9 @@ tahq_status tahq_tile_entropy(const tahq_config *cfg, const void *d_in, float *d
     if (rc != TAHQ_OK) return rc;
     if (!d_in || !d_entropy) return TAHQ_ERR_NULL;
     if (misaligned(d_in) || misaligned(d_entropy)) return TAHQ_ERR_MISALIGNED;
-    launch_entropy(s, cfg, d_in, d_entropy, nullptr, 0u, 0.0f, (hipStream_t)stream);
-    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+    Enqueue q{(hipStream_t)stream};
+    launch_entropy(s, cfg, d_in, d_entropy, nullptr, 0u, 0.0f, &q);
+    return q.result();
 }
 
 tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, float *d_entropy, void *d_workspace,
@@ -272,8 +322,9 @@ tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, fl
     if (rc != TAHQ_OK) return rc;
     if (!d_in || !d_entropy) return TAHQ_ERR_NULL;
     if (misaligned(d_in) || misaligned(d_entropy)) return TAHQ_ERR_MISALIGNED;
+    Enqueue q{(hipStream_t)stream};
     if (s.m == 1) {
-        launch_entropy(s, cfg, d_in, d_entropy, nullptr, 0u, 0.0f, (hipStream_t)stream);
+        launch_entropy(s, cfg, d_in, d_entropy, nullptr, 0u, 0.0f, &q);
     } else {
         if (!d_workspace) return TAHQ_ERR_NULL;
         Workspace ws;
@@ -284,9 +335,9 @@ tahq_status tahq_alloc_tile_entropy(const tahq_config *cfg, const void *d_in, fl
         dispatch<LaunchAllocEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, d_entropy,
                                      reinterpret_cast<float *>(wsb + ws.part),
                                      reinterpret_cast<float *>(wsb + ws.inv_norm), (uint32_t)s.T, s.m, cfg->eps_l1,
-                                     cfg->eps_log, (hipStream_t)stream);
+                                     cfg->eps_log, &q);
     }
-    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+    return q.result();
 }
 
 tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d_packed, size_t packed_capacity,
@@ -306,8 +357,11 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     if (packed_capacity < lay.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
     if (workspace_capacity < ws.total) return TAHQ_ERR_WORKSPACE_TOO_SMALL;
     if (misaligned(d_in) || misaligned(d_packed) || misaligned(d_workspace)) return TAHQ_ERR_MISALIGNED;
+    // the selection kernels of large ranking units put the unit into the grid's second dimension
+    if (s.kA != 0 && s.kA != s.nA && s.U > 65535u && (s.nA > kSmallUnitMaxKeys || multi_launch))
+        return TAHQ_ERR_UNSUPPORTED;
 
-    hipStream_t st = (hipStream_t)stream;
+    Enqueue q{(hipStream_t)stream};
     uint8_t *packed = static_cast<uint8_t *>(d_packed);
     uint8_t *wsb = static_cast<uint8_t *>(d_workspace);
     uint64_t *bitmap = reinterpret_cast<uint64_t *>(packed + lay.bitmap);
@@ -340,7 +394,7 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     const bool histograms = select && !small_units;
     const uint32_t zero_words = histograms ? (uint32_t)(ws.zero_bytes / 4) : 0u;
     if (phases & TAHQ_PHASE_PROLOGUE)
-        hipLaunchKernelGGL(k_prologue, dim3(histograms ? 32 : 1), dim3(256), 0, st, packed, hdr, pads,
+        q(k_prologue, dim3(histograms ? 32 : 1), dim3(256), packed, hdr, pads,
                            reinterpret_cast<uint32_t *>(wsb + ws.hist0), zero_words);
 
     if (select) {
@@ -365,21 +419,21 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
             if (wide)
                 dispatch<LaunchAllocEntropy>(s.G, s.dtype == TAHQ_BF16, d_in, H, reinterpret_cast<float *>(wsb + ws.part),
                                              reinterpret_cast<float *>(wsb + ws.inv_norm), (uint32_t)s.T, s.m,
-                                             cfg->eps_l1, cfg->eps_log, st);
+                                             cfg->eps_l1, cfg->eps_log, &q);
             else if (fused_select)
-                launch_entropy(s, cfg, d_in, H, lin_hist, kLinBins, bin_scale, st);
+                launch_entropy(s, cfg, d_in, H, lin_hist, kLinBins, bin_scale, &q);
             else
-                launch_entropy(s, cfg, d_in, H, fused ? hist0 : (uint32_t *)nullptr, kDigit0Bins, 0.0f, st);
+                launch_entropy(s, cfg, d_in, H, fused ? hist0 : (uint32_t *)nullptr, kDigit0Bins, 0.0f, &q);
         }
         if ((phases & TAHQ_PHASE_SELECT) && fused_select) {
             const dim3 grid((uint32_t)((s.n + kFusedKeysPerBlock - 1) / kFusedKeysPerBlock), s.U);
             uint32_t *fused_state = reinterpret_cast<uint32_t *>(wsb + ws.fused);
             uint2 *cand = reinterpret_cast<uint2 *>(wsb + ws.cand);
             uint32_t *block_above = reinterpret_cast<uint32_t *>(wsb + ws.block_above);
-            hipLaunchKernelGGL(k_select_classify, grid, dim3(kFusedThreads), 0, st, (const float *)H, (uint32_t)s.n,
+            q(k_select_classify, grid, dim3(kFusedThreads), (const float *)H, (uint32_t)s.n,
                                (uint32_t)s.k, bin_scale, (const uint32_t *)lin_hist, fused_state, cand, block_above,
                                bitmap);
-            hipLaunchKernelGGL(k_select_resolve, grid, dim3(kFusedThreads), 0, st, (const float *)H, (uint32_t)s.n,
+            q(k_select_resolve, grid, dim3(kFusedThreads), (const float *)H, (uint32_t)s.n,
                                (uint32_t)s.k, bin_scale, (const uint32_t *)lin_hist, (const uint32_t *)fused_state,
                                (const uint2 *)cand, (const uint32_t *)block_above, bitmap, ranks);
         } else
@@ -390,48 +444,48 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
             uint32_t *rank_out = wide ? ranks_a : ranks;
             const dim3 grid(s.U), block(kSmallUnitThreads);
             if (n32 <= 16 * kSmallUnitThreads)
-                hipLaunchKernelGGL((k_select_small<16>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
+                q(k_select_small<16>, grid, block, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
             else
-                hipLaunchKernelGGL((k_select_small<32>), grid, block, 0, st, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
+                q(k_select_small<32>, grid, block, (const float *)H, n32, k32, bitmap, rank_out, sel, aligned);
             if (wide)
-                hipLaunchKernelGGL(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                q(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256),
                                    (const uint8_t *)sel, (const uint32_t *)ranks_a, (uint32_t)s.T, s.m, bitmap, ranks);
             else if (!aligned)
-                hipLaunchKernelGGL(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                q(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256),
                                    (const uint8_t *)sel, (uint32_t)s.T, bitmap);
         } else if (phases & TAHQ_PHASE_SELECT) {
             // the selection ranks allocation tiles; with A = G they are the stream's tiles
             const uint32_t n32 = (uint32_t)s.nA, k32 = (uint32_t)s.kA;
             const dim3 rgrid(ws.hb, s.U);
             if (!fused)
-                hipLaunchKernelGGL((k_radix_pass<0, 8>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
-            hipLaunchKernelGGL((k_radix_pass<1, 0>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
-            hipLaunchKernelGGL((k_radix_pass<2, 0>), rgrid, dim3(256), 0, st, (const float *)H, n32, k32, hist0, coarse, partial, state);
+                q(k_radix_pass<0, 8>, rgrid, dim3(256), (const float *)H, n32, k32, hist0, coarse, partial, state);
+            q(k_radix_pass<1, 0>, rgrid, dim3(256), (const float *)H, n32, k32, hist0, coarse, partial, state);
+            q(k_radix_pass<2, 0>, rgrid, dim3(256), (const float *)H, n32, k32, hist0, coarse, partial, state);
             const uint32_t sb = (ws.nseg + 3) / 4;
-            hipLaunchKernelGGL(k_seg_count, dim3(sb, s.U), dim3(256), 0, st, (const float *)H, n32, ws.nseg,
+            q(k_seg_count, dim3(sb, s.U), dim3(256), (const float *)H, n32, ws.nseg,
                                (const uint32_t *)coarse, (const uint32_t *)partial, ws.hb, state, seg);
             const int aligned = (!wide && s.n % 64 == 0) ? 1 : 0;
             uint32_t *ranks_a = reinterpret_cast<uint32_t *>(wsb + ws.ranks_a);
-            hipLaunchKernelGGL(k_assign, dim3(sb, s.U), dim3(256), 0, st, (const float *)H, n32, k32, ws.nseg,
+            q(k_assign, dim3(sb, s.U), dim3(256), (const float *)H, n32, k32, ws.nseg,
                                (const uint32_t *)state, (const uint32_t *)seg, bitmap, wide ? ranks_a : ranks, sel,
                                aligned);
             if (wide)
-                hipLaunchKernelGGL(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                q(k_expand_alloc, dim3(blocks_for(words64 * 64)), dim3(256),
                                    (const uint8_t *)sel, (const uint32_t *)ranks_a, (uint32_t)s.T, s.m, bitmap, ranks);
             else if (!aligned)
-                hipLaunchKernelGGL(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256), 0, st,
+                q(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256),
                                    (const uint8_t *)sel, (uint32_t)s.T, bitmap);
         }
     } else if (phases & TAHQ_PHASE_SELECT) {
-        hipLaunchKernelGGL(k_bitmap_const, dim3(blocks_for(words64)), dim3(256), 0, st, (uint32_t)s.T,
+        q(k_bitmap_const, dim3(blocks_for(words64)), dim3(256), (uint32_t)s.T,
                            s.kA == s.nA ? 1 : 0, bitmap, ranks);
     }
 
     if (phases & TAHQ_PHASE_QUANT) {
         dispatch<LaunchQuantPack>(s.G, s.dtype == TAHQ_BF16, s.low, d_in, packed, lay, (uint32_t)s.T, cfg->tau,
-                                  cfg->eps_ratio, st);
+                                  cfg->eps_ratio, &q);
     }
-    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+    return q.result();
 }
 
 tahq_status tahq_encode(const tahq_config *cfg, const void *d_in, void *d_packed, size_t packed_capacity,
@@ -486,9 +540,72 @@ tahq_status tahq_decode(const tahq_config *cfg, const void *d_packed, size_t pac
     make_layout(s, &lay);
     if (packed_bytes < lay.total) return TAHQ_ERR_BUFFER_TOO_SMALL;
     if (misaligned(d_packed) || misaligned(d_out)) return TAHQ_ERR_MISALIGNED;
+    Enqueue q{(hipStream_t)stream};
     dispatch<LaunchDecode>(s.G, out_dtype == TAHQ_BF16, s.low, static_cast<const uint8_t *>(d_packed), d_out, lay,
-                           (uint32_t)s.T, (uint32_t)(s.U * s.k), (hipStream_t)stream);
-    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+                           (uint32_t)s.T, (uint32_t)(s.U * s.k), &q);
+    return q.result();
+}
+
+// ---- sample-wise use: a run of samples as a tensor of its own
+
+namespace {
+// The configuration of samples [first, first + count) taken as a tensor [count, seq, hidden], and the byte offset
+// of the first of them in the whole tensor (element size `esize`).
+tahq_status samples_config(const tahq_config *cfg, uint32_t first, uint32_t count, uint32_t esize, tahq_config *sub,
+                           uint64_t *offset)
+{
+    Shape s;
+    tahq_status rc = make_shape(cfg, &s);
+    if (rc != TAHQ_OK) return rc;
+    if (s.scope != 0 || count == 0 || first >= s.B || count > s.B - first) return TAHQ_ERR_INVALID_ARG;
+    memset(sub, 0, sizeof *sub);
+    memcpy(sub, cfg, cfg->struct_size);          // older, shorter layouts: the missing fields stay 0
+    sub->batch = count;
+    *offset = (uint64_t)first * s.S * s.C * esize;
+    return TAHQ_OK;
+}
+}  // namespace
+
+size_t tahq_samples_packed_size(const tahq_config *cfg, uint32_t count)
+{
+    tahq_config sub;
+    uint64_t off;
+    if (samples_config(cfg, 0, count, 1, &sub, &off) != TAHQ_OK) return 0;
+    return tahq_packed_size(&sub);
+}
+
+size_t tahq_samples_workspace_size(const tahq_config *cfg, uint32_t count)
+{
+    tahq_config sub;
+    uint64_t off;
+    if (samples_config(cfg, 0, count, 1, &sub, &off) != TAHQ_OK) return 0;
+    return tahq_workspace_size(&sub);
+}
+
+tahq_status tahq_encode_samples(const tahq_config *cfg, uint32_t first, uint32_t count, const void *d_in, void *d_packed,
+                                size_t packed_capacity, void *d_workspace, size_t workspace_capacity, tahq_stream stream)
+{
+    if (!cfg) return TAHQ_ERR_NULL;
+    tahq_config sub;
+    uint64_t off;
+    tahq_status rc = samples_config(cfg, first, count, cfg->dtype == TAHQ_BF16 ? 2u : 4u, &sub, &off);
+    if (rc != TAHQ_OK) return rc;
+    if (!d_in) return TAHQ_ERR_NULL;
+    return tahq_encode(&sub, static_cast<const uint8_t *>(d_in) + off, d_packed, packed_capacity, d_workspace,
+                       workspace_capacity, stream);
+}
+
+tahq_status tahq_decode_samples(const tahq_config *cfg, uint32_t first, uint32_t count, const void *d_packed,
+                                size_t packed_bytes, void *d_out, uint32_t out_dtype, tahq_stream stream)
+{
+    if (!cfg) return TAHQ_ERR_NULL;
+    if (out_dtype > TAHQ_BF16) return TAHQ_ERR_INVALID_ARG;
+    tahq_config sub;
+    uint64_t off;
+    tahq_status rc = samples_config(cfg, first, count, out_dtype == TAHQ_BF16 ? 2u : 4u, &sub, &off);
+    if (rc != TAHQ_OK) return rc;
+    if (!d_out) return TAHQ_ERR_NULL;
+    return tahq_decode(&sub, d_packed, packed_bytes, static_cast<uint8_t *>(d_out) + off, out_dtype, nullptr, 0, stream);
 }
 
 tahq_status tahq_parse_header(const void *header64, tahq_config *cfg)
@@ -564,13 +681,14 @@ tahq_status tahq_naive_encode(const tahq_naive_config *cfg, const void *d_in, vo
     memcpy(&hdr.w[7], &cfg->scale, 4);
     uint8_t *packed = static_cast<uint8_t *>(d_packed);
     const bool bf16 = cfg->dtype == TAHQ_BF16;
+    Enqueue q{(hipStream_t)stream};
     switch (cfg->bits) {
-#define X(B) case B: launch_naive_encode<B>(bf16, d_in, packed, hdr, s.nchunks, cfg->scale, (hipStream_t)stream); break;
+#define X(B) case B: launch_naive_encode<B>(bf16, d_in, packed, hdr, s.nchunks, cfg->scale, &q); break;
         TAHQ_NAIVE_WIDTHS(X)
 #undef X
     default: return TAHQ_ERR_INVALID_ARG;
     }
-    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+    return q.result();
 }
 
 tahq_status tahq_naive_decode(const tahq_naive_config *cfg, const void *d_packed, size_t packed_bytes, void *d_out,
@@ -585,13 +703,14 @@ tahq_status tahq_naive_decode(const tahq_naive_config *cfg, const void *d_packed
     if (misaligned(d_packed) || misaligned(d_out)) return TAHQ_ERR_MISALIGNED;
     const float inv_scale = 1.0f / cfg->scale;      // rounded once, on the host
     const uint8_t *packed = static_cast<const uint8_t *>(d_packed);
+    Enqueue q{(hipStream_t)stream};
     switch (cfg->bits) {
-#define X(B) case B: launch_naive_decode<B>(out_dtype == TAHQ_BF16, packed, d_out, s.nchunks, inv_scale, (hipStream_t)stream); break;
+#define X(B) case B: launch_naive_decode<B>(out_dtype == TAHQ_BF16, packed, d_out, s.nchunks, inv_scale, &q); break;
         TAHQ_NAIVE_WIDTHS(X)
 #undef X
     default: return TAHQ_ERR_INVALID_ARG;
     }
-    return hipGetLastError() == hipSuccess ? TAHQ_OK : TAHQ_ERR_HIP;
+    return q.result();
 }
 
 }  // extern "C"

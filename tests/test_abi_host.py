@@ -181,3 +181,59 @@ def test_naive_codec_sizes_defaults_and_argument_errors():
     assert lib.tahq_naive_decode(C.byref(cfg), A, size, B_ + 4, 0, None) == 6
     bad = tahq.make_naive_config(**dict(ok, bits=20))
     assert lib.tahq_naive_encode(C.byref(bad), A, B_, 1 << 20, None) == 2
+
+
+class _FakeDeviceTensor:
+    """Just enough of a torch tensor for the binding's host-side checks (nothing is launched)."""
+
+    def __init__(self, nbytes, esize):
+        self._n, self._e = nbytes // esize, esize
+        self.is_cuda = True
+
+    def is_contiguous(self):
+        return True
+
+    def data_ptr(self):
+        return 0x10000
+
+    def numel(self):
+        return self._n
+
+    def element_size(self):
+        return self._e
+
+
+def test_binding_refuses_tensors_that_do_not_fit_the_configuration():
+    # the C ABI carries no capacity for the activation tensors: the binding checks them before the call
+    cfg = tahq.make_config(2, 4, 256, 64, tahq.BF16, 3.5)
+    n = 2 * 4 * 256
+    packed = _FakeDeviceTensor(tahq.tahq_packed_size(cfg), 1)
+    ws = _FakeDeviceTensor(tahq.tahq_workspace_size(cfg), 1)
+    with pytest.raises(ValueError, match="holds"):
+        tahq.tahq_encode(cfg, _FakeDeviceTensor(2 * n - 2, 2), packed, ws, stream=0)
+    with pytest.raises(ValueError, match="4-byte elements"):
+        tahq.tahq_encode(cfg, _FakeDeviceTensor(4 * n, 4), packed, ws, stream=0)
+    with pytest.raises(ValueError, match="holds"):
+        tahq.tahq_encode_noalloc(cfg, _FakeDeviceTensor(n, 2), packed, stream=0)
+    with pytest.raises(ValueError, match="holds"):
+        tahq.tahq_decode(cfg, packed, _FakeDeviceTensor(2 * n, 4), tahq.F32, stream=0)
+    with pytest.raises(ValueError, match="2-byte elements"):
+        tahq.tahq_decode(cfg, packed, _FakeDeviceTensor(8 * n, 2), tahq.F32, stream=0)
+    with pytest.raises(ValueError, match="holds"):
+        tahq.tahq_tile_entropy(cfg, _FakeDeviceTensor(2 * n, 2), _FakeDeviceTensor(4 * (n // 64) - 4, 4), stream=0)
+    ncfg = tahq.make_naive_config(2, 4, 256, tahq.F32, 8, 4.0)
+    with pytest.raises(ValueError, match="holds"):
+        tahq.tahq_naive_encode(ncfg, _FakeDeviceTensor(4 * n - 4, 4), _FakeDeviceTensor(1 << 20, 1), stream=0)
+    with pytest.raises(ValueError, match="holds"):
+        tahq.tahq_naive_decode(ncfg, _FakeDeviceTensor(1 << 20, 1), _FakeDeviceTensor(n, 2), tahq.BF16, stream=0)
+
+
+def test_more_than_65535_ranking_units_on_the_multi_launch_selection_are_refused():
+    # that selection puts the ranking unit into the grid's second dimension (units large enough to take it by
+    # default cannot be that many: the tensor would exceed 2^31 tiles)
+    cfg = tahq.make_config(70000, 1, 256, 64, tahq.BF16, 3.5)
+    lib = binding._load()
+    big = 1 << 40
+    assert lib.tahq_encode_phases(C.byref(cfg), 0x10000, 0x20000, big, 0x30000, big, 15 | 16, None) == 3
+    cfg = tahq.make_config(65535, 1, 256, 64, tahq.BF16, 3.5)
+    assert tahq.tahq_packed_size(cfg) > 0
