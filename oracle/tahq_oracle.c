@@ -44,8 +44,9 @@ typedef struct {
     float eps_log;        /* varsigma of Eq. 2 */
     float eps_ratio;      /* varrho of Eq. 3 */
     uint32_t alloc_tile;  /* A: allocation-tile size (Sec. 3.2), a multiple of G dividing C; 0 means A = G */
-    uint32_t low_bits;    /* lo: the two widths are lo and lo+1.  3 (or 0) = INT3/INT4, the paper's setting;
-                             2 = the INT2/INT3 mix of the appendix on bit allocation */
+    uint32_t low_bits;    /* lo: the two widths are lo and lo+1, 1 <= lo <= 7.  3 (or 0) = INT3/INT4, the paper's
+                             setting; 2 = the INT2/INT3 mix of the appendix on bit allocation; the same appendix
+                             sweeps the ratio of two neighbouring widths, which any lo gives */
 } tahq_oracle_cfg;
 
 enum { OR_OK = 0, OR_BAD = 1, OR_SMALL = 2 };
@@ -57,7 +58,7 @@ static int cfg_ok(const tahq_oracle_cfg *c)
     if (c->tile != 8 && c->tile != 16 && c->tile != 32 && c->tile != 64 && c->tile != 128) return 0;
     if (c->hidden % c->tile) return 0;
     if (c->dtype > 1 || c->scope > 1) return 0;
-    if (c->low_bits != 0 && c->low_bits != 2 && c->low_bits != 3) return 0;
+    if (c->low_bits > 7) return 0;
     float lo = c->low_bits ? (float)c->low_bits : 3.0f;
     if (!(c->budget_bits >= lo && c->budget_bits <= lo + 1.0f)) return 0;
     if (c->alloc_tile != 0 && (c->alloc_tile % c->tile || c->hidden % c->alloc_tile)) return 0;

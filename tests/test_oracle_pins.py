@@ -463,7 +463,11 @@ def test_allocation_tile_must_align_with_quantization_tiles_and_divide_the_hidde
 # ------------------- tiles of 8 and 16 channels, hidden sizes that are not powers of two
 
 @pytest.mark.parametrize("G,C_,dtype_name,low", [(8, 200, "f32", 3), (16, 208, "bf16", 3), (8, 64, "bf16", 2),
-                                                 (16, 1600, "f32", 2), (64, 1600, "bf16", 3), (32, 1600, "f32", 3)])
+                                                 (16, 1600, "f32", 2), (64, 1600, "bf16", 3), (32, 1600, "f32", 3),
+                                                 # any pair of neighbouring widths, 1/2 bits up to 7/8 bits
+                                                 (8, 64, "f32", 1), (64, 640, "bf16", 1), (128, 256, "bf16", 4),
+                                                 (32, 160, "bf16", 5), (16, 208, "f32", 6), (64, 1600, "f32", 7),
+                                                 (8, 200, "bf16", 7)])
 def test_small_tiles_and_hidden_1600_streams_parse_and_decode_in_float64(G, C_, dtype_name, low):
     # the tile-size ablation uses tiles of 8 channels; 1600 is a hidden size with 25 tiles of 64 per token
     rng = np.random.default_rng(G + C_)
@@ -510,7 +514,7 @@ def _sweep_cases(count, seed):
         G = int(rng.choice([8, 16, 32, 64, 128]))
         M = int(rng.choice([1, 2, 3, 4, 6, 10]))
         B, S = int(rng.choice([1, 2, 3])), int(rng.choice([1, 5, 23, 70]))
-        low = int(rng.choice([3, 3, 2]))
+        low = int(rng.choice([3, 3, 2, 1, 4, 5, 6, 7]))
         divisors = [d for d in range(1, M + 1) if M % d == 0]
         m = int(rng.choice(divisors)) if rng.random() < 0.5 else 1
         out.append(dict(B=B, S=S, G=G, M=M, dtype=int(rng.integers(0, 2)), low=low, m=m, scope=int(rng.random() < 0.3),
@@ -519,7 +523,7 @@ def _sweep_cases(count, seed):
     return out
 
 
-@pytest.mark.parametrize("c", _sweep_cases(40, seed=77), ids=lambda c: "{B}x{S}x{M}tiles_g{G}_d{dtype}_lo{low}_m{m}_s{scope}".format(**c))
+@pytest.mark.parametrize("c", _sweep_cases(64, seed=77), ids=lambda c: "{B}x{S}x{M}tiles_g{G}_d{dtype}_lo{low}_m{m}_s{scope}".format(**c))
 def test_option_combinations_parse_and_decode_independently_in_float64(c):
     # every combination of tile width, dtype, widths, allocation tile, scope and tau goes through the independent
     # float64 statement: size, header, allocation from the entropies, rank table, pivots, coverage, decode, error bound
@@ -889,3 +893,36 @@ def test_k_gives_the_mean_width_closest_to_the_budget():
         assert k in best, (n, budget, k, best)
     cfg = o32.make_cfg(1, 4, 96, 32, o32.F32, 3.4)      # n = 12: 0.4 * 12 = 4.8 -> 5 tiles
     assert o32.k_per_unit(cfg) == 5
+
+
+@pytest.mark.parametrize("low", (1, 2, 3, 4, 5, 6, 7))
+def test_any_pair_of_neighbouring_widths(low):
+    # the appendix on bit allocation sweeps the ratio of two neighbouring widths (and tries a 2/3-bit mix): widths lo
+    # and lo+1 for any lo.  Pinned here: the budget range moves with lo; the mean payload width is the budget; at the
+    # ends of the range every tile has one width; codes stay below 2^b; the float64 reading of the stream meets the
+    # half-step bound per tile; and at 8 bits a code is a byte of the payload.
+    rng = np.random.default_rng(90 + low)
+    B, S, G, M = 2, 24, 32, 5
+    x = rng.standard_normal((B, S, G * M)).astype(np.float32)
+    x[:, :, 7::41] *= 30.0
+    T, n = B * S * M, S * M
+    assert o32.packed_size(o32.make_cfg(B, S, G * M, G, o32.F32, low - 0.01, low_bits=low)) == 0
+    assert o32.packed_size(o32.make_cfg(B, S, G * M, G, o32.F32, low + 1.01, low_bits=low)) == 0
+    for budget in (float(low), low + 0.25, low + 0.7, low + 1.0):
+        cfg = o32.make_cfg(B, S, G * M, G, o32.F32, budget, tau=float("inf"), low_bits=low)
+        k = o32.k_per_unit(cfg)
+        assert k == round((budget - low) * n)
+        packed = o32.encode(cfg, x)
+        out64, s = o64.decode_stream(packed, T, G, B, k, low=low)
+        assert set(np.unique(s["width"])) <= {low, low + 1} and int((s["width"] == low + 1).sum()) == B * k
+        assert abs(s["width"].mean() - budget) < 1.0 / n
+        L = (1 << s["width"]) - 1
+        assert np.all(s["codes"] <= L[:, None])
+        # untransformed tiles (tau = inf): every element within half a step of its reconstruction
+        step = s["scale"].astype(np.float64)[:, None]
+        assert np.all(np.abs(out64 - x.reshape(T, G).astype(np.float64)) <= 0.5 * step * (1 + 1e-6))
+        assert np.array_equal(o32.decode(cfg, packed, o32.F32).reshape(T, G), out64.astype(np.float32))
+    if low == 7:
+        off = o64.section_offsets(T, G, B, n, low=7)
+        assert np.array_equal(packed[off["payload"]:off["total"]].reshape(T, G), s["codes"].astype(np.uint8))
+    assert o32.packed_size(o32.make_cfg(B, S, G * M, G, o32.F32, 8.5, low_bits=8)) == 0
