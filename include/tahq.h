@@ -13,7 +13,8 @@
  *   - 3- or 4-bit width: the top-p% highest-entropy tiles of
  *     every sample get 4 bits, p = budget_bits - 3            [Sec. 3.2]
  *     (lo and lo+1 bits with p = budget_bits - lo if low_bits
- *     selects the INT2/INT3 mix of the appendix on bit allocation)
+ *     selects another pair of neighbouring widths, e.g. the
+ *     INT2/INT3 mix of the appendix on bit allocation)
  *     (entropy and ranking may run on allocation tiles of
  *     A = alloc_tile channels, A a multiple of `tile`; the
  *     quantization tiles inside one share its width)
@@ -98,9 +99,11 @@ typedef struct {
     float eps_ratio;        /* varrho of Eq. 3;    default 1e-8                                   */
     uint32_t alloc_tile;    /* A, the allocation tile of Sec. 3.2: a multiple of G that divides C;
                                0 = G (the paper's default); A = C is token-level allocation        */
-    uint32_t low_bits;      /* lo: the two code widths are lo and lo+1 bits and budget_bits lies in
-                               [lo, lo+1].  3 (or 0) = INT3/INT4, the paper's setting; 2 = the
-                               INT2/INT3 mix of the appendix on bit allocation                     */
+    uint32_t low_bits;      /* lo, 1..7: the two code widths are lo and lo+1 bits and budget_bits lies
+                               in [lo, lo+1].  3 (or 0) = INT3/INT4, the paper's setting; 2 = the
+                               INT2/INT3 mix of the appendix on bit allocation; any other pair of
+                               neighbouring widths up to 7/8 bits (the appendix sweeps the ratio of
+                               two widths)                                                         */
 } tahq_config;
 
 /* Fill *cfg with the defaults (tile 64, budget 3.8, tau 2.0, eps 1e-8, scope 0,

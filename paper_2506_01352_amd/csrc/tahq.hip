@@ -130,7 +130,7 @@ struct CanFuse {
     static void run(uint64_t n_per_unit, bool *out) { *out = LaunchEntropy<G, BF16>::can_fuse_histogram(n_per_unit); }
 };
 
-// `low`: the narrower of the two code widths, 3 (INT3/INT4) or 2 (INT2/INT3).
+// `low`: the narrower of the two code widths, 1..7 (3: INT3/INT4).
 template <int G, bool BF16>
 struct LaunchQuantPack {
     template <int LOW>
@@ -145,8 +145,15 @@ struct LaunchQuantPack {
     static void run(uint32_t low, const void *d_in, uint8_t *packed, Layout lay, uint32_t T, float tau, float eps_ratio,
                     Enqueue *qp)
     {
-        if (low == 3u) go<3>(d_in, packed, lay, T, tau, eps_ratio, qp);
-        else go<2>(d_in, packed, lay, T, tau, eps_ratio, qp);
+        switch (low) {
+        case 1: go<1>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        case 2: go<2>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        case 3: go<3>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        case 4: go<4>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        case 5: go<5>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        case 6: go<6>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        default: go<7>(d_in, packed, lay, T, tau, eps_ratio, qp); break;
+        }
     }
 };
 
@@ -166,8 +173,15 @@ struct LaunchDecode {
     static void run(uint32_t low, const uint8_t *packed, void *d_out, Layout lay, uint32_t T, uint32_t total_wide,
                     Enqueue *qp)
     {
-        if (low == 3u) go<3>(packed, d_out, lay, T, total_wide, qp);
-        else go<2>(packed, d_out, lay, T, total_wide, qp);
+        switch (low) {
+        case 1: go<1>(packed, d_out, lay, T, total_wide, qp); break;
+        case 2: go<2>(packed, d_out, lay, T, total_wide, qp); break;
+        case 3: go<3>(packed, d_out, lay, T, total_wide, qp); break;
+        case 4: go<4>(packed, d_out, lay, T, total_wide, qp); break;
+        case 5: go<5>(packed, d_out, lay, T, total_wide, qp); break;
+        case 6: go<6>(packed, d_out, lay, T, total_wide, qp); break;
+        default: go<7>(packed, d_out, lay, T, total_wide, qp); break;
+        }
     }
 };
 

@@ -13,7 +13,7 @@ namespace tahq {
 
 struct Shape {
     uint32_t B, S, C, G, dtype, scope;
-    uint32_t low; // the two code widths are low and low + 1 bits (3 by default, 2 for the INT2/INT3 mix)
+    uint32_t low; // the two code widths are low and low + 1 bits, 1..7 (3 by default, 2 for the INT2/INT3 mix)
     uint32_t A;   // allocation tile (Sec. 3.2), a multiple of G
     uint32_t m;   // quantization tiles per allocation tile, A / G
     uint64_t T;   // quantization tiles in the tensor
@@ -68,7 +68,7 @@ tahq_status make_shape(const tahq_config *c, Shape *s)
         return TAHQ_ERR_INVALID_ARG;
     const uint32_t A = (c->struct_size == 48u || c->alloc_tile == 0) ? c->tile : c->alloc_tile;
     const uint32_t low = (c->struct_size < 56u || c->low_bits == 0) ? 3u : c->low_bits;
-    if (low != 2u && low != 3u) return TAHQ_ERR_INVALID_ARG;
+    if (low < 1u || low > 7u) return TAHQ_ERR_INVALID_ARG;
     if (c->batch == 0 || c->seq == 0 || c->hidden == 0) return TAHQ_ERR_INVALID_ARG;
     if (c->tile == 0 || c->hidden % c->tile != 0) return TAHQ_ERR_INVALID_ARG;
     if (c->dtype > TAHQ_BF16 || c->scope > 1) return TAHQ_ERR_INVALID_ARG;

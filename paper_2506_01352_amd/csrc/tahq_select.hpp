@@ -413,7 +413,10 @@ __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict_
 // ---- small ranking units: the whole selection in one launch
 
 constexpr uint32_t kSmallUnitThreads = 1024;
-constexpr uint32_t kSmallUnitMaxKeys = 32768;    // 32 keys per thread; beyond that the keys no longer fit the
+#ifndef TAHQ_SMALL_UNIT_MAX
+#define TAHQ_SMALL_UNIT_MAX 32768
+#endif
+constexpr uint32_t kSmallUnitMaxKeys = TAHQ_SMALL_UNIT_MAX;    // 32 keys per thread; beyond that the keys no longer fit the
                                                  // register file of a 1024-thread workgroup and the multi-launch path is as fast
 
 // A ranking unit of at most 1024 * KPT keys, ranked by ONE workgroup that keeps the keys in registers: the

@@ -578,18 +578,22 @@ __device__ __forceinline__ void transform_row(const uint8_t *row, bool flag, flo
     }
 }
 
+// Dwords that hold the G W-bit codes of a tile.
+template <int G, int W> struct BitString { static constexpr int DWORDS = (G * W + 31) / 32; };
+
 // The tile's LSB-first bit string, as dwords, from groups of four W-bit codes (g4[g] = q0 + 2^W q1 + 2^2W q2
-// + 2^3W q3).  Dwords past the string are zero.
+// + 2^3W q3), W <= 4.  Writes the dwords the string occupies; the caller has cleared the rest.
 template <int G, int W>
 __device__ __forceinline__ void pack_groups(const uint32_t *g4, uint32_t *dw)
 {
+    static_assert(W >= 1 && W <= 4, "groups of four codes are exact in fp32 up to 4 bits per code");
     if constexpr (G < 32) {
         // at most 64 bits: two or four groups of 4 W bits through one 64-bit accumulator
         uint64_t acc = 0;
 #pragma unroll
         for (int g = 0; g < G / 4; ++g) acc |= (uint64_t)g4[g] << (4 * W * g);
         dw[0] = (uint32_t)acc;
-        if constexpr (G == 16) dw[1] = (uint32_t)(acc >> 32);
+        if constexpr (G * W > 32) dw[1] = (uint32_t)(acc >> 32);
     } else if constexpr (W == 4) {
 #pragma unroll
         for (int i = 0; i < G / 8; ++i) dw[i] = g4[2 * i] | (g4[2 * i + 1] << 16);
@@ -602,16 +606,32 @@ __device__ __forceinline__ void pack_groups(const uint32_t *g4, uint32_t *dw)
             dw[3 * i + 1] = (p[2] >> 8) | (p[3] << 4) | (p[4] << 16) | (p[5] << 28);
             dw[3 * i + 2] = (p[5] >> 4) | (p[6] << 8) | (p[7] << 20);
         }
-#pragma unroll
-        for (int i = 3 * (G / 32); i < G / 8; ++i) dw[i] = 0;
-    } else {
-        static_assert(W == 2, "code widths are 2, 3 or 4 bits");
+    } else if constexpr (W == 2) {
         // 8-bit groups: four of them fill a dword
 #pragma unroll
         for (int i = 0; i < G / 16; ++i)
             dw[i] = g4[4 * i] | (g4[4 * i + 1] << 8) | (g4[4 * i + 2] << 16) | (g4[4 * i + 3] << 24);
+    } else {
+        // 4-bit groups: eight of them fill a dword
 #pragma unroll
-        for (int i = G / 16; i < G / 8; ++i) dw[i] = 0;
+        for (int i = 0; i < G / 32; ++i) {
+            uint32_t t = 0;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) t |= g4[8 * i + g] << (4 * g);
+            dw[i] = t;
+        }
+    }
+}
+
+// The same from the codes themselves, for any width up to 8 bits: code k occupies bits [W k, W k + W).
+template <int G, int W>
+__device__ __forceinline__ void place_codes(const uint32_t *q, uint32_t *dw)
+{
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        const int bit = W * k, i = bit >> 5, sh = bit & 31;
+        dw[i] |= q[k] << sh;
+        if (sh + W > 32) dw[i + 1] |= q[k] >> (32 - sh);
     }
 }
 
@@ -636,42 +656,56 @@ __device__ __forceinline__ uint32_t quantize_values(const float *x, uint32_t b, 
     if ((s16 & 0x7fffu) == 0) s16 = 0x3c00u;
     const float sf = f16_widen(s16);
     const float rcp = 1.0f / sf;
-
-    // codes, four at a time: q0 + m q1 + m^2 q2 + m^3 q3 is an exact integer below 2^16 in fp32
-    const float m1 = (b == WIDE) ? (float)(1u << WIDE) : (float)(1u << LOW);
-    const float m2 = m1 * m1, m3 = m2 * m1;
     // Every element lies in [mn, mx]; if z <= mn, (x - z) * rcp lies in [0, (mx - z) * rcp], and when that
     // bound rounds to at most L the clamp is the identity and is skipped.  Both conditions can fail only when
     // the binary16 metadata saturated (magnitudes beyond the contract).
-    uint32_t g4[G / 4];
-    if (mnf <= mn && (mx - mnf) * rcp <= Lv + 0.25f) {
+    const bool no_clamp = mnf <= mn && (mx - mnf) * rcp <= Lv + 0.25f;
+
+    constexpr int DW = BitString<G, WIDE>::DWORDS > G / 8 ? BitString<G, WIDE>::DWORDS : (G / 8 ? G / 8 : 1);
+    uint32_t dw[DW];
 #pragma unroll
-        for (int g = 0; g < G / 4; ++g) {
-            float q[4];
+    for (int i = 0; i < DW; ++i) dw[i] = 0;
+    if constexpr (WIDE <= 4) {
+        // codes, four at a time: q0 + m q1 + m^2 q2 + m^3 q3 is an exact integer below 2^16 in fp32
+        const float m1 = (b == WIDE) ? (float)(1u << WIDE) : (float)(1u << LOW);
+        const float m2 = m1 * m1, m3 = m2 * m1;
+        uint32_t g4[G / 4];
+        if (no_clamp) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) q[i] = __builtin_rintf((x[4 * g + i] - mnf) * rcp);
-            const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
-            g4[g] = (uint32_t)acc;
+            for (int g = 0; g < G / 4; ++g) {
+                float q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) q[i] = __builtin_rintf((x[4 * g + i] - mnf) * rcp);
+                const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
+                g4[g] = (uint32_t)acc;
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < G / 4; ++g) {
+                float q[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    q[i] = __builtin_amdgcn_fmed3f(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f, Lv);
+                const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
+                g4[g] = (uint32_t)acc;
+            }
         }
+        if (b == WIDE) pack_groups<G, WIDE>(g4, dw);
+        else pack_groups<G, LOW>(g4, dw);
     } else {
+        // wider codes: one by one (a NaN code becomes 0 in the clamp)
+        uint32_t q[G];
 #pragma unroll
-        for (int g = 0; g < G / 4; ++g) {
-            float q[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                q[i] = __builtin_amdgcn_fmed3f(__builtin_rintf((x[4 * g + i] - mnf) * rcp), 0.0f, Lv);
-            const float acc = __builtin_fmaf(q[3], m3, __builtin_fmaf(q[2], m2, __builtin_fmaf(q[1], m1, q[0])));
-            g4[g] = (uint32_t)acc;
-        }
+        for (int k = 0; k < G; ++k)
+            q[k] = (uint32_t)__builtin_amdgcn_fmed3f(__builtin_rintf((x[k] - mnf) * rcp), 0.0f, Lv);
+        if (b == WIDE) place_codes<G, WIDE>(q, dw);
+        else place_codes<G, LOW>(q, dw);
     }
-    // LSB-first bit string of the tile as dwords
-    uint32_t dw[G / 8];
-    if (b == WIDE) pack_groups<G, WIDE>(g4, dw);
-    else pack_groups<G, LOW>(g4, dw);
+    // the bit string leaves as b units of G/8 bytes
 #pragma unroll
     for (int u = 0; u < (int)WIDE; ++u) {
         if (u < LOW || b == WIDE) {
-            if constexpr (G == 8) dst[u] = (uint8_t)(dw[0] >> (8 * u));
+            if constexpr (G == 8) dst[u] = (uint8_t)(dw[u >> 2] >> (8 * (u & 3)));
             else if constexpr (G == 16) dst[u] = (uint16_t)(dw[u >> 1] >> (16 * (u & 1)));
             else if constexpr (G == 32) dst[u] = dw[u];
             else if constexpr (G == 64) dst[u] = make_uint2(dw[2 * u], dw[2 * u + 1]);
@@ -792,8 +826,7 @@ __device__ __forceinline__ void codes_to_nibbles(const uint32_t *dw, uint32_t *n
             t = (t & 0x07070707u) | ((t & 0x38383838u) << 1);
             nib[i] = t;
         }
-    } else {
-        static_assert(W == 2, "code widths are 2, 3 or 4 bits");
+    } else if constexpr (W == 2) {
 #pragma unroll
         for (int i = 0; i < G / 8; ++i) {
             // codes 8i .. 8i+7 occupy bits [16i, 16i+16) of the string
@@ -803,6 +836,30 @@ __device__ __forceinline__ void codes_to_nibbles(const uint32_t *dw, uint32_t *n
             t = (t & 0x03030303u) | ((t & 0x0c0c0c0cu) << 2);
             nib[i] = t;
         }
+    } else {
+        static_assert(W == 1, "nibbles hold codes of up to 4 bits");
+#pragma unroll
+        for (int i = 0; i < G / 8; ++i) {
+            // codes 8i .. 8i+7 are byte i of the string
+            uint32_t t = (dw[i >> 2] >> (8 * (i & 3))) & 0xffu;
+            t = (t & 0x0000000fu) | ((t & 0x000000f0u) << 12);
+            t = (t & 0x00030003u) | ((t & 0x000c000cu) << 6);
+            t = (t & 0x01010101u) | ((t & 0x02020202u) << 3);
+            nib[i] = t;
+        }
+    }
+}
+
+// ... and, for any width up to 8 bits, the codes one by one, de-quantized: x[k] = q_k * sf + mnf.
+template <int G, int W>
+__device__ __forceinline__ void dequantize_codes(const uint32_t *dw, float sf, float mnf, float *x)
+{
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+        const int bit = W * k, i = bit >> 5, sh = bit & 31;
+        uint32_t q = dw[i] >> sh;
+        if (sh + W > 32) q |= dw[i + 1] << (32 - sh);
+        x[k] = __builtin_fmaf((float)(q & ((1u << W) - 1u)), sf, mnf);
     }
 }
 
@@ -816,33 +873,39 @@ __device__ __forceinline__ void decode_row(const typename Unit<G>::type *src, ui
     constexpr int WIDE = LOW + 1;
     const float sf = f16_widen(s16), mnf = f16_widen(z16);
     // my LOW or WIDE units (the last one is read in any case: it stays inside the array)
-    uint32_t dw[G / 8];
+    constexpr int DW = BitString<G, WIDE>::DWORDS > G / 8 ? BitString<G, WIDE>::DWORDS : (G / 8 ? G / 8 : 1);
+    uint32_t dw[DW + 1];                         // one more: the one-by-one reader may look past the string
 #pragma unroll
-    for (int i = 0; i < G / 8; ++i) dw[i] = 0;
+    for (int i = 0; i < DW + 1; ++i) dw[i] = 0;
 #pragma unroll
     for (int u = 0; u < WIDE; ++u) {
         const U t = src[u];
-        if constexpr (G == 8) dw[0] |= (uint32_t)t << (8 * u);
+        if constexpr (G == 8) dw[u >> 2] |= (uint32_t)t << (8 * (u & 3));
         else if constexpr (G == 16) dw[u >> 1] |= (uint32_t)t << (16 * (u & 1));
         else if constexpr (G == 32) dw[u] = t;
         else if constexpr (G == 64) { dw[2 * u] = t.x; dw[2 * u + 1] = t.y; }
         else { dw[4 * u] = t.x; dw[4 * u + 1] = t.y; dw[4 * u + 2] = t.z; dw[4 * u + 3] = t.w; }
     }
-    uint32_t nib[G / 8];
-    if (b == (uint32_t)WIDE) codes_to_nibbles<G, WIDE>(dw, nib);
-    else codes_to_nibbles<G, LOW>(dw, nib);
-    // de-quantize: even codes sit in the low nibbles of the bytes, odd codes in the high nibbles
-    // (scaled by 16, undone exactly by a scale of sf/16)
-    const float sf16 = sf * 0.0625f;
     float x[G];
+    if constexpr (WIDE <= 4) {
+        uint32_t nib[G / 8];
+        if (b == (uint32_t)WIDE) codes_to_nibbles<G, WIDE>(dw, nib);
+        else codes_to_nibbles<G, LOW>(dw, nib);
+        // de-quantize: even codes sit in the low nibbles of the bytes, odd codes in the high nibbles
+        // (scaled by 16, undone exactly by a scale of sf/16)
+        const float sf16 = sf * 0.0625f;
 #pragma unroll
-    for (int i = 0; i < G / 8; ++i) {
-        const uint32_t lo = nib[i] & 0x0f0f0f0fu, hi = nib[i] & 0xf0f0f0f0u;
+        for (int i = 0; i < G / 8; ++i) {
+            const uint32_t lo = nib[i] & 0x0f0f0f0fu, hi = nib[i] & 0xf0f0f0f0u;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            x[8 * i + 2 * c] = __builtin_fmaf((float)((lo >> (8 * c)) & 0xffu), sf, mnf);
-            x[8 * i + 2 * c + 1] = __builtin_fmaf((float)((hi >> (8 * c)) & 0xffu), sf16, mnf);
+            for (int c = 0; c < 4; ++c) {
+                x[8 * i + 2 * c] = __builtin_fmaf((float)((lo >> (8 * c)) & 0xffu), sf, mnf);
+                x[8 * i + 2 * c + 1] = __builtin_fmaf((float)((hi >> (8 * c)) & 0xffu), sf16, mnf);
+            }
         }
+    } else {
+        if (b == (uint32_t)WIDE) dequantize_codes<G, WIDE>(dw, sf, mnf, x);
+        else dequantize_codes<G, LOW>(dw, sf, mnf, x);
     }
     if (pv & 0x80u) {
         butterfly<G>(x);

@@ -40,6 +40,9 @@ def test_sizes_match_the_oracle_layout_on_all_configs_and_variants():
     # tiles of 8 and 16 channels, a hidden size with 25 tiles of 64 per token
     cases += [(3, 7, 96, 8, 0, 3.3, 0, 0, 0), (2, 5, 1600, 16, 1, 3.8, 0, 0, 0), (2, 5, 1600, 64, 1, 3.8, 0, 320, 0),
               (8, 4096, 8192, 8, 1, 3.25, 0, 0, 0), (1, 3, 64, 8, 0, 2.5, 1, 32, 2)]
+    # other pairs of neighbouring widths
+    cases += [(3, 7, 96, 32, 0, 1.5, 0, 0, 1), (2, 5, 640, 64, 1, 7.25, 0, 0, 7), (2, 5, 640, 128, 1, 5.0, 1, 0, 4),
+              (8, 4096, 8192, 64, 1, 6.5, 0, 0, 6), (3, 7, 96, 8, 0, 8.0, 0, 0, 7)]
     # the INT2/INT3 mix
     cases += [(3, 7, 96, 32, 0, 2.3, 0, 0, 2), (8, 4096, 8192, 64, 1, 2.2, 0, 0, 2), (2, 5, 640, 64, 1, 3.0, 0, 320, 2),
               (2, 5, 640, 128, 1, 2.0, 1, 0, 2), (2, 5, 640, 64, 1, 3.4, 0, 0, 3)]
@@ -67,6 +70,7 @@ def test_invalid_configs_are_rejected_with_size_zero():
         dict(budget_bits=2.9), dict(budget_bits=4.1), dict(budget_bits=float("nan")), dict(dtype=2), dict(scope=2),
         dict(alloc_tile=32), dict(alloc_tile=96), dict(alloc_tile=192), dict(alloc_tile=512),
         dict(low_bits=1), dict(low_bits=4), dict(low_bits=2), dict(low_bits=2, budget_bits=3.1),
+        dict(low_bits=8, budget_bits=8.5), dict(low_bits=7, budget_bits=8.1), dict(low_bits=1, budget_bits=0.9),
         dict(low_bits=2, budget_bits=1.9),
     ]
     for kw in bad:

@@ -56,3 +56,24 @@ def test_algorithmic_bytes_are_tensor_plus_stream():
     alg = bench.algorithmic_bytes(w, size, T, True)
     assert alg["k_quant_pack"] == alg["k_decode"] == 2 * w.elements + size == 667680832
     assert alg["k_entropy"] == 2 * w.elements + 4 * T == 553648128
+
+
+def test_stored_counter_readings_come_from_the_profile_summaries():
+    # bench.py does not carry counter readings of its own: it parses profiles/hbm_traffic_*.md.  The streaming kernels'
+    # measured traffic must stay within 2 % of their algorithmic bytes, and every kernel of a step must be listed.
+    sys.path.insert(0, ROOT)
+    import bench
+    import workloads
+    from oracle import o32
+    per, step, src = bench.stored_traffic("hbm_traffic_cfg4_bf16_8x4096x8192_g64")
+    assert src == "profiles/hbm_traffic_cfg4_bf16_8x4096x8192_g64.md"
+    w = workloads.CONFIGS[3]
+    size = o32.packed_size(o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits))
+    alg = bench.algorithmic_bytes(w, size, w.elements // w.tile, True)
+    for kernel in ("k_entropy", "k_quant_pack", "k_decode"):
+        assert abs(per[kernel] / alg[kernel] - 1.0) < 0.02, kernel
+    assert {"k_select_classify", "k_select_resolve"} <= set(per), sorted(per)
+    assert step == sum(per.values()) and step > sum(alg.values())
+    naive, _, nsrc = bench.stored_traffic("hbm_traffic_naive_cfg5_bf16_16x2048x5120_b8")
+    assert nsrc and abs(naive["k_naive_encode"] / 503316544 - 1.0) < 0.02
+    assert bench.stored_traffic("hbm_traffic_no_such_workload") == (None, None, None)

@@ -36,6 +36,22 @@ def test_forward_bench_line():
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9 and 0.05 < rf["frac"] < 1.0
     assert rf["kernel"] in ("k_entropy", "k_quant_pack", "k_decode") and rf["traffic"] > 0
     assert abs(d["value"] - 536870912 / (d["ms_per_step"] * 1e-3) / 1e9) < 1e-6 * d["value"]
+    # four steps: the wall-clock mean is the figure; encode and decode from events, the copy ceiling and the fp32-output
+    # decode measured in the same run, both shares of the HBM peak
+    assert d["ms_per_step_is"] == "wall-clock mean" and d["ms_per_step"] == d["ms_per_step_wall"]
+    assert 0 < d["decode_ms"] < d["encode_ms"] < d["ms_per_step"] * 1.5
+    assert d["decode_f32_out_ms"] > d["decode_ms"] and 1000 < d["copy_ceiling_gbs"] < 8000
+    assert 0 < d["pct_hbm_peak_algorithmic"] < d["pct_hbm_peak_of_measured_traffic"] < 100
+    assert rf["traffic_source"].startswith("profiles/hbm_traffic_cfg4_")
+
+
+def test_forward_bench_line_graph_and_sample_wise_rehearsal():
+    print("[case] bench.py --graph --chunked on a small shape", file=sys.stderr, flush=True)
+    d = run_bench("--shape", "4x256x2048", "--budget", "3.5", "--graph", "--chunked")
+    assert d["graph"]["ms_per_step"] > 0 and d["graph"]["replays"] == 4
+    c = d["chunked"]
+    assert c["samples"] == 4 and c["whole_tensor_ms"] > 0 and c["sample_wise_ms"] > 0
+    assert d["roofline"]["traffic"] is None and d["pct_hbm_peak_of_measured_traffic"] is None
 
 
 def test_backward_bench_line():

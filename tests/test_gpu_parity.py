@@ -286,6 +286,28 @@ def test_int2_int3_edge_tiles_other_output_type_and_allocation_tiles(tahq, G):
     check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, 2.4, low_bits=2, scope=1, tau=4.0)
 
 
+# any pair of neighbouring widths, 1/2 bits up to 7/8 bits (the appendix on bit allocation sweeps the ratio of two widths)
+@pytest.mark.parametrize("low", (1, 4, 5, 6, 7))
+def test_other_width_pairs_bit_exact(tahq, low):
+    for index, shape in ((2, dict(batch=2, seq=40)), (4, dict(batch=2, seq=36)), (3, dict(batch=2, seq=24)),
+                         (5, dict(batch=3, seq=10)), (1, dict())):
+        w, x = workloads.generate(index, **shape)
+        for budget in (low + 0.3, float(low), low + 1.0):
+            _say(f"[case] {w.name} shape={w.batch}x{w.seq}x{w.hidden} widths {low}/{low + 1} budget={budget}")
+            check_case(tahq, x, w.batch, w.seq, w.hidden, w.tile, w.dtype, budget, low_bits=low)
+    # edge tiles at every tile width, the other output type, an allocation tile of three tiles, whole-tensor ranking
+    for G in (8, 16, 32, 64, 128):
+        tiles = workloads.edge_tiles(G)
+        n = len(tiles) // 3 * 3
+        _say(f"[case] widths {low}/{low + 1} edge tiles G={G}")
+        check_case(tahq, tiles, 1, len(tiles), G, G, tahq.F32, low + 0.5, low_bits=low)
+        check_case(tahq, workloads.f32_to_bf16_bits(tiles), 1, len(tiles), G, G, tahq.BF16, low + 0.5,
+                   out_dtype=tahq.F32, low_bits=low)
+        check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, low + 0.4, out_dtype=tahq.BF16, low_bits=low,
+                   alloc_tile=3 * G)
+        check_case(tahq, tiles[:n], 1, n // 3, 3 * G, G, tahq.F32, low + 0.4, low_bits=low, scope=1, tau=4.0)
+
+
 def test_massive_entropy_ties_are_broken_by_index(tahq):
     # config-5-like tensor (20% all-zero tokens: entropy exactly 0) with a budget that puts the
     # threshold inside the tie, plus a tensor whose tiles are all identical
@@ -538,7 +560,7 @@ def test_nan_inf_and_huge_inputs_are_lossy_but_never_a_fault(tahq):
         assert np.array_equal(out[n * G:].view(np.uint32), want_out.view(np.uint32))
 
 
-@pytest.mark.parametrize("G,low", [(64, 3), (32, 2), (8, 3), (128, 3), (16, 2)])
+@pytest.mark.parametrize("G,low", [(64, 3), (32, 2), (8, 3), (128, 3), (16, 2), (64, 7), (16, 5), (128, 1)])
 def test_decoding_a_damaged_stream_stays_inside_its_buffers(tahq, G, low):
     # The decoder clamps the rank table to the number of wide tiles the configuration implies, ignores a decreasing
     # table, and masks the pivot index, so every address it forms lies inside the stream and the output whatever
@@ -587,7 +609,7 @@ def _random_configurations(count, seed):
         S = int(rng.choice([1, 3, 17, 64, 200, 513, 1500]))
         if B * S * Cc > 6_000_000:
             continue
-        low = int(rng.choice([3, 3, 2]))
+        low = int(rng.choice([3, 3, 2, 1, 4, 5, 6, 7]))
         budget = float(np.float32(low + rng.choice([0.0, 1.0, rng.uniform(0.02, 0.98)])))
         divisors = [d for d in range(1, M + 1) if M % d == 0]
         m = int(rng.choice(divisors)) if rng.random() < 0.4 else 1
