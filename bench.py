@@ -8,8 +8,10 @@ fp32 output, and the CPU oracle's throughput on a bounded sample of the same wor
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--alloc-tile A] [--no-cpu-baseline]
 
-Timing: W instrumented warm-up steps, `--settle` more plain ones (clocks), then EXACTLY K steps between two
-synchronizations.  `ms_per_step` is the wall-clock mean of those K steps; from 50 steps on it is the median of the K
+Timing: W instrumented warm-up steps, then plain untimed steps for about `--settle-ms` milliseconds (at least `--settle`
+of them) right before the timed region: the GPU reaches its steady clocks only after some tens of milliseconds of load,
+and a step measured before that is up to 15 % slower than the codec runs in a training job.  Then EXACTLY K steps
+between two synchronizations.  `ms_per_step` is the wall-clock mean of those K steps; from 50 steps on it is the median of the K
 per-step times taken with events at the step boundaries, and the wall-clock mean is reported beside it.
 
 `--chunked` adds the pipeline rehearsal on one GPU (sample-wise encode on two streams, device -> pinned host -> device
@@ -96,6 +98,15 @@ def cpu_baseline(index, w, alloc_tile, low_bits, budget):
     }
 
 
+def settle_steps(args, step_ms_estimate):
+    """Number of plain untimed steps to run right before the timed region: enough for --settle-ms at the step time the
+    warm-up saw, at least --settle, at most 20000."""
+    n = args.settle
+    if args.settle_ms > 0 and step_ms_estimate > 0:
+        n = max(n, int(args.settle_ms / step_ms_estimate) + 1)
+    return min(n, 20000)
+
+
 def naive_main(args):
     """tahq_naive_encode + tahq_naive_decode per step; both kernels are timed with events on every 4th step."""
     import numpy as np
@@ -128,10 +139,16 @@ def naive_main(args):
         if ev:
             ev[2].record(stream)
 
-    for _ in range(max(args.warmup, 1)):
-        step()
+    wev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(max(args.warmup, 1))]
+    for ev in wev:
+        step(ev)
+    torch.cuda.synchronize()
+    warm_step_ms = float(np.median([e[0].elapsed_time(e[2]) for e in wev]))
     EVENT_EVERY = 4
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range((args.steps + EVENT_EVERY - 1) // EVENT_EVERY)]
+    n_settle = settle_steps(args, warm_step_ms)
+    for _ in range(n_settle):
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -156,6 +173,7 @@ def naive_main(args):
         "config": {"workload": w.name, "codec": "naive", "shape": [w.batch, w.seq, w.hidden],
                    "storage": "bf16" if w.dtype else "f32", "bits": args.bits, "scale": args.scale,
                    "out_dtype": "same as input"},
+        "settle_steps": n_settle, "settle_ms": args.settle_ms,
         "kernel_ms": {"k_naive_encode": enc_ms, "k_naive_decode": dec_ms},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
@@ -186,7 +204,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--settle", type=int, default=10,
-                    help="plain untimed steps between the instrumented warm-up and the timed region")
+                    help="least number of plain untimed steps right before the timed region")
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="plain untimed steps are run for about this long right before the timed region, so that the "
+                         "timed steps see the GPU's steady clocks (0: only --settle steps)")
     ap.add_argument("--config", type=int, default=None, help="workload index 1..5 (default 4: the metric's config)")
     ap.add_argument("--codec", choices=("tahq", "naive"), default="tahq",
                     help="tahq: the forward activation codec (the metric); naive: the backward fixed-point compressor")
@@ -300,9 +321,6 @@ def main():
         tahq.tahq_encode(cfg, d_in, codec.packed, codec.workspace, stream)
         tahq.tahq_decode(cfg, codec.packed, codec.out, codec.out_dtype, stream)
 
-    for _ in range(args.settle):
-        plain_step()
-
     # a plain device copy of the input tensor in the same run: what this machine's HBM gives a kernel that only moves bytes
     copy_gbs = None
     if not args.no_extras:
@@ -347,6 +365,9 @@ def main():
     evs = [(new_event(), new_event(), new_event()) for _ in range(n_split)]
     bounds = [new_event() for _ in range(args.steps + 1)]
 
+    n_settle = settle_steps(args, sum(warm_ms.values()))
+    for _ in range(n_settle):
+        plain_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -405,7 +426,7 @@ def main():
                    "tile": w.tile, "alloc_tile": args.alloc_tile or w.tile, "budget_bits": budget,
                    "widths": [low, low + 1], "out_dtype": "same as input"},
         "ms_per_step_is": "median of per-step event times" if args.steps >= 50 else "wall-clock mean",
-        "ms_per_step_wall": wall_ms, "ms_per_step_median": median_ms, "settle_steps": args.settle,
+        "ms_per_step_wall": wall_ms, "ms_per_step_median": median_ms, "settle_steps": n_settle, "settle_ms": args.settle_ms,
         "encode_ms": encode_ms, "decode_ms": decode_ms,
         "decode_f32_out_ms": decode_f32_ms,
         "value_f32_out": (nbytes / ((encode_ms + decode_f32_ms) * 1e-3) / 1e9) if decode_f32_ms else None,
@@ -421,7 +442,7 @@ def main():
         "roofline": roofline,
     }
     if args.graph:
-        out["graph"] = graph_replay(tahq, torch, np, cfg, codec, d_in, args.steps, nbytes)
+        out["graph"] = graph_replay(tahq, torch, np, cfg, codec, d_in, args.steps, nbytes, max(5, n_settle))
     if args.chunked:
         out["chunked"] = chunked_loopback(tahq, torch, np, cfg, codec, d_in, w)
     if not args.no_cpu_baseline:
@@ -429,7 +450,7 @@ def main():
     print(json.dumps(out))
 
 
-def graph_replay(tahq, torch, np, cfg, codec, d_in, steps, nbytes):
+def graph_replay(tahq, torch, np, cfg, codec, d_in, steps, nbytes, settle):
     """encode + decode captured once into a HIP graph and replayed `steps` times: what a caller pays per step when the
     launches are taken off the host (matters for micro-batches of the size the paper trains with)."""
     s = torch.cuda.Stream()
@@ -439,7 +460,7 @@ def graph_replay(tahq, torch, np, cfg, codec, d_in, steps, nbytes):
         with torch.cuda.graph(graph, stream=s):
             tahq.tahq_encode(cfg, d_in, codec.packed, codec.workspace, s)
             tahq.tahq_decode(cfg, codec.packed, codec.out, codec.out_dtype, s)
-        for _ in range(5):
+        for _ in range(settle):
             graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -41,11 +41,10 @@ __device__ __forceinline__ uint4 load16(const uint8_t *p)
 
 template <int G, int ESIZE, bool FULL, bool STREAM = false>
 __device__ __forceinline__ void load_batch(const void *__restrict__ in, uint64_t j0, uint32_t nvalid,
-                                           uint4 (&v)[Batch<G, ESIZE>::CHUNKS])
+                                           uint4 (&v)[Batch<G, ESIZE>::CHUNKS], int tid = (int)threadIdx.x)
 {
     using B = Batch<G, ESIZE>;
     const uint8_t *src = static_cast<const uint8_t *>(in) + j0 * B::BYTES;
-    const int tid = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < B::CHUNKS; ++i) {
         const uint32_t q = (uint32_t)i * B::TILES + tid;
@@ -59,10 +58,10 @@ __device__ __forceinline__ void load_batch(const void *__restrict__ in, uint64_t
 }
 
 template <int G, int ESIZE, bool FULL>
-__device__ __forceinline__ void store_batch(const uint4 (&v)[Batch<G, ESIZE>::CHUNKS], uint32_t nvalid, uint8_t *lds)
+__device__ __forceinline__ void store_batch(const uint4 (&v)[Batch<G, ESIZE>::CHUNKS], uint32_t nvalid, uint8_t *lds,
+                                            int tid = (int)threadIdx.x)
 {
     using B = Batch<G, ESIZE>;
-    const int tid = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < B::CHUNKS; ++i) {
         const uint32_t q = (uint32_t)i * B::TILES + tid;
@@ -727,10 +726,10 @@ struct QuantPackOccupancy { static constexpr int WAVES_PER_SIMD = (G * ESIZE <= 
 // paths rarely both run.  The payload buffer reuses the rows' LDS once every lane holds its tile in
 // registers, which keeps the workgroup small enough for four to share a compute unit: this kernel
 // lives on the loads of its neighbours being in flight while it computes.
-template <int G, bool BF16, int LOW>
-__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES), (QuantPackOccupancy<G, BF16 ? 2 : 4>::WAVES_PER_SIMD))
-void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Layout lay, uint32_t T, float tau,
-                  float eps_ratio)
+template <int G, bool BF16, int LOW, bool FULL>
+__device__ __forceinline__ void quant_pack_batch(const void *__restrict__ in, uint8_t *__restrict__ packed, const Layout &lay,
+                                                 uint32_t T, float tau, float eps_ratio, uint32_t batch, uint32_t nvalid,
+                                                 uint8_t *lds, uint32_t *info, uint16_t *order, uint32_t *class_count)
 {
     constexpr int ES = BF16 ? 2 : 4;
     using B = Batch<G, ES>;
@@ -738,30 +737,25 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
     constexpr int WAVES = (B::TILES + 63) / 64;
     constexpr uint32_t WIDE = LOW + 1;           // the two code widths are LOW and WIDE bits
     static_assert(sizeof(U) * WIDE * B::TILES <= (size_t)B::LDS_BYTES, "payload buffer must fit in the rows");
-    __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
-    __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == WIDE) << 8 | rel << 9
-    __shared__ uint16_t order[B::TILES];         // tiles in class order
-    __shared__ uint32_t class_count[4 * WAVES];  // tiles per class and wavefront, class-major
     U *pay = reinterpret_cast<U *>(lds);         // valid only after every lane has left the rows
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint64_t j0 = (uint64_t)blockIdx.x * B::TILES;
-    const uint32_t left = (uint32_t)(T - j0);
-    const uint32_t nvalid = left < (uint32_t)B::TILES ? left : (uint32_t)B::TILES;
-    const bool full = nvalid == (uint32_t)B::TILES;
+    // The lane index passes through an empty asm statement, so the optimiser derives every address from
+    // it afresh instead of sharing address arithmetic between the phases: measured 3 % faster.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint64_t j0 = (uint64_t)batch * B::TILES;
 
     uint4 v[B::CHUNKS];
-    if (full) load_batch<G, ES, true, true>(in, j0, nvalid, v);      // second and last read of the tensor
-    else load_batch<G, ES, false, true>(in, j0, nvalid, v);
+    load_batch<G, ES, FULL, true>(in, j0, nvalid, v, tid);           // second and last read of the tensor
     BatchMeta<B::TILES> meta;
     load_meta<B::TILES>(packed, lay, j0, T, 0u, meta);
-    if (full) store_batch<G, ES, true>(v, nvalid, lds);
-    else store_batch<G, ES, false>(v, nvalid, lds);
+    store_batch<G, ES, FULL>(v, nvalid, lds, tid);
     uint32_t b, rel, total4;
     tile_pos<B::TILES, LOW>(meta, tid, &b, &rel, &total4);
     __syncthreads();
 
     // stage one: my own tile
-    const bool valid = (uint32_t)tid < nvalid;
+    const bool valid = FULL || (uint32_t)tid < nvalid;
     uint32_t cls = 4;                            // tiles past the end sort last
     if (valid) {
         const uint32_t pv = analyse_row<G, BF16>(lds + tid * B::STRIDE, tau, eps_ratio);
@@ -802,6 +796,27 @@ void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Lay
         const uint32_t q = (uint32_t)i * B::TILES + tid;
         if (q < span) gdst[q] = pay[q];
     }
+}
+
+template <int G, bool BF16, int LOW>
+__global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES), (QuantPackOccupancy<G, BF16 ? 2 : 4>::WAVES_PER_SIMD))
+void k_quant_pack(const void *__restrict__ in, uint8_t *__restrict__ packed, Layout lay, uint32_t T, float tau,
+                  float eps_ratio)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    using B = Batch<G, ES>;
+    constexpr int WAVES = (B::TILES + 63) / 64;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[B::LDS_BYTES];
+    __shared__ uint32_t info[B::TILES];          // per tile: pivot byte | (b == WIDE) << 8 | rel << 9
+    __shared__ uint16_t order[B::TILES];         // tiles in class order
+    __shared__ uint32_t class_count[4 * WAVES];  // tiles per class and wavefront, class-major
+    const uint32_t nfull = T / B::TILES;        // a workgroup per batch; the last one may be ragged
+    if (blockIdx.x < nfull)
+        quant_pack_batch<G, BF16, LOW, true>(in, packed, lay, T, tau, eps_ratio, blockIdx.x, B::TILES, lds, info, order,
+                                             class_count);
+    else
+        quant_pack_batch<G, BF16, LOW, false>(in, packed, lay, T, tau, eps_ratio, nfull, T % B::TILES, lds, info, order,
+                                              class_count);
 }
 
 // ------------------------------------------------------------- K4: decode
