@@ -410,9 +410,113 @@ __global__ __launch_bounds__(256) void k_expand_alloc(const uint8_t *__restrict_
     }
 }
 
+constexpr uint32_t kBlockSelectThreads = 1024;
+
+// LDS scratch of block_radix_select.
+struct BlockSelectLds {
+    uint32_t copies[8192];                       // the histogram of one digit, several copies of every bin
+    uint32_t lh[4096 + 64];                      // its bins added up; bin b at b + b/64: a lane that reads bin l of a chunk
+                                                 // of 64 bins while its neighbours read theirs meets no bank conflict
+    uint32_t chunk_total[64];                    // totals of the chunks of 64 bins
+    uint32_t chosen[5];                          // bin, wanted inside it, its count; smallest and largest value
+};
+
+// Workgroup-wide radix select over the values that `each` hands to its argument (every thread visits its own share
+// of the values; each(g) calls g(value) for each of them): the `want`-th largest value (1 <= want <= number of values),
+// how many values equal to it belong to the `want` largest, and how many values equal to it there are.  The values of
+// one selection lie close together (the entropies of one sample, or the keys of one histogram bin), so the digits are
+// taken from value - minimum: 12 bits at a time from the top of max - min, usually two passes.  Called by all 1024
+// threads; the result is the same in every thread.
+template <class Each>
+__device__ __forceinline__ void block_radix_select(uint32_t want, Each each, BlockSelectLds &L, uint32_t *thr_out,
+                                                   uint32_t *take_out, uint32_t *equal_out)
+{
+    constexpr int kBins = 4096;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (tid == 0) { L.chosen[3] = 0xffffffffu; L.chosen[4] = 0u; }
+    __syncthreads();
+    {
+        uint32_t lo = 0xffffffffu, hi = 0u;
+        each([&](uint32_t val) { lo = val < lo ? val : lo; hi = val > hi ? val : hi; });
+        // per wavefront first: a thousand atomics on one LDS address would take longer than the rest of the selection
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, off, 64), ohi = (uint32_t)__shfl_xor((int)hi, off, 64);
+            lo = olo < lo ? olo : lo;
+            hi = ohi > hi ? ohi : hi;
+        }
+        if (lane == 0 && lo <= hi) { atomicMin(&L.chosen[3], lo); atomicMax(&L.chosen[4], hi); }
+    }
+    __syncthreads();
+    const uint32_t vmin = L.chosen[3], span = L.chosen[4] - vmin;
+    int bits = 32 - __builtin_clz(span | 1u);    // digits cover bits [0, bits) of value - vmin
+    uint32_t prefix = 0;                         // the digits found so far, as the top bits of value - vmin
+    uint32_t equal = 0;
+#pragma unroll 1
+    while (true) {
+        const int shift = bits > 12 ? bits - 12 : 0;         // this pass: bits [shift, bits)
+        const uint32_t mask = (1u << (bits - shift)) - 1u;
+        // Several copies of every bin, indexed by the lane, as many as the 8192 words hold (2 for a 12-bit digit, at
+        // most 32): a wavefront's atomics on one LDS address are serialized, and under massive ties a digit takes
+        // one or two values.
+        const int copy_bits = 13 - (bits - shift) > 5 ? 5 : 13 - (bits - shift);
+        const uint32_t my_copy = (uint32_t)lane & ((1u << copy_bits) - 1u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) L.copies[i * (int)kBlockSelectThreads + tid] = 0;
+        __syncthreads();
+        each([&](uint32_t val) {
+            const uint32_t d = val - vmin;
+            if (bits == 32 || (d >> bits) == prefix) atomicAdd(&L.copies[(((d >> shift) & mask) << copy_bits) | my_copy], 1u);
+        });
+        __syncthreads();
+        // thread t adds up the copies of bins t, t + 1024, ...; the 64 bins of a wavefront are one chunk, whose total
+        // the wavefront leaves beside them
+#pragma unroll
+        for (int part = 0; part < kBins / (int)kBlockSelectThreads; ++part) {
+            const uint32_t bin = (uint32_t)tid + kBlockSelectThreads * part;
+            uint32_t sum = 0;
+            if (bin <= mask) {
+                for (int c = 0; c < (1 << copy_bits); ++c) sum += L.copies[(bin << copy_bits) + c];
+            }
+            L.lh[bin + (bin >> 6)] = sum;
+            const uint32_t upto = wave_incl_scan(sum);
+            if (lane == 63) L.chunk_total[(kBlockSelectThreads / 64) * part + wave] = upto;
+        }
+        __syncthreads();
+        // the bin that holds the want-th largest value, in two levels: the chunk from the top, then the bin inside it
+        if (tid < 64) {
+            const uint32_t cs = L.chunk_total[63 - lane];                   // lane l: chunk 63 - l, from the top
+            const uint32_t above = wave_incl_scan(cs) - cs;
+            const uint64_t who = __ballot(above < want && want <= above + cs);
+            const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
+            const uint32_t chunk = 63u - (uint32_t)src;
+            const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
+            const uint32_t bs = L.lh[chunk * 65 + (63 - lane)];             // lane l: bin 63 - l of the chunk
+            const uint32_t above2 = wave_incl_scan(bs) - bs;
+            const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
+            const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
+            if (lane == src2) {
+                L.chosen[0] = chunk * 64 + (63u - (uint32_t)src2);
+                L.chosen[1] = want2 - above2;
+                L.chosen[2] = bs;
+            }
+        }
+        __syncthreads();
+        prefix = (bits - shift == 32) ? L.chosen[0] : ((prefix << (bits - shift)) | L.chosen[0]);
+        want = L.chosen[1];
+        equal = L.chosen[2];
+        __syncthreads();
+        if (shift == 0) break;
+        bits = shift;
+    }
+    *thr_out = vmin + prefix;
+    *take_out = want;
+    *equal_out = equal;
+}
+
 // ---- small ranking units: the whole selection in one launch
 
-constexpr uint32_t kSmallUnitThreads = 1024;
+constexpr uint32_t kSmallUnitThreads = kBlockSelectThreads;
 #ifndef TAHQ_SMALL_UNIT_MAX
 #define TAHQ_SMALL_UNIT_MAX 32768
 #endif
@@ -420,7 +524,7 @@ constexpr uint32_t kSmallUnitMaxKeys = TAHQ_SMALL_UNIT_MAX;    // 32 keys per th
                                                  // register file of a 1024-thread workgroup and the multi-launch path is as fast
 
 // A ranking unit of at most 1024 * KPT keys, ranked by ONE workgroup that keeps the keys in registers: the
-// three radix passes run on an LDS histogram, the per-group counts and their prefix sums stay in LDS, and
+// radix passes (12 bits at a time of key - smallest key, two passes as a rule) run on an LDS histogram, the per-group counts and their prefix sums stay in LDS, and
 // the bit map and rank table (or, for units that do not start on 64-tile boundaries, one byte per tile and
 // the rank entries of the 64-tile groups) are written at the end.  Same result as k_radix_pass x 3,
 // k_seg_count and k_assign, in one launch instead of five: small tensors are bound by launch latency.
@@ -433,15 +537,8 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
                                                                     uint8_t *__restrict__ sel_bytes, int aligned)
 {
     constexpr int NG = 16 * KPT;                 // 64-tile groups the workgroup can hold
-    // Digits of 8, 12 and 12 bits from the top.  The histogram keeps several copies of every bin, indexed by
-    // the low bits of the lane: a wavefront's atomics on one LDS address are serialized, and the first digit
-    // (sign and most of the exponent) takes one or two values, as does any digit under massive ties.
-    // 32 copies of 256 bins, or 2 copies of 4096 bins.
-    constexpr int kBins = 4096;
-    __shared__ uint32_t copies[8192];
-    __shared__ uint32_t lh[kBins + kBins / 64];  // bin b at b + b/64: a lane that walks one chunk of 64 bins while
-                                                 // its neighbours walk theirs meets no bank conflict
-    __shared__ uint32_t chosen[2];
+    constexpr int PER = NG / 64;                 // lane l of wavefront 0 scans the PER consecutive groups PER*l ..
+    __shared__ BlockSelectLds L;
     __shared__ uint32_t grp_eq[NG], grp_sel[NG];
     const uint32_t u = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -460,93 +557,61 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
     for (int r = 0; r < KPT; ++r) key[r] = order_key(h[r]);
     auto in_unit = [&](int r) { return (uint32_t)(KPT * wave + r) * 64u + lane < n; };
 
-    uint32_t want = k, hi = 0;
-#pragma unroll
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 24 : (pass == 1 ? 12 : 0);
-        const uint32_t mask = pass == 0 ? 255u : 4095u;
-        const int hi_shift = pass == 1 ? 24 : 12;
-        const int copy_bits = pass == 0 ? 5 : 1;
-        const uint32_t my_copy = (uint32_t)lane & ((1u << copy_bits) - 1u);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) copies[i * (int)kSmallUnitThreads + tid] = 0;
-        __syncthreads();
+    // the k-th largest key, how many tiles equal to it are taken, and how many there are
+    uint32_t thr, take, equal;
+    block_radix_select(k, [&](auto &&visit) {
 #pragma unroll
         for (int r = 0; r < KPT; ++r) {
-            const bool active = in_unit(r) && (pass == 0 || (key[r] >> hi_shift) == hi);
-            if (active) atomicAdd(&copies[((((key[r] >> shift) & mask)) << copy_bits) | my_copy], 1u);
+            if (in_unit(r)) visit(key[r]);
         }
-        __syncthreads();
-        // thread t adds up the copies of bins t, t + 1024, ... (a 256-bin digit leaves the rest empty)
-#pragma unroll
-        for (int part = 0; part < kBins / (int)kSmallUnitThreads; ++part) {
-            const uint32_t bin = (uint32_t)tid + kSmallUnitThreads * part;
-            uint32_t sum = 0;
-            if (bin <= mask) {
-                for (int c = 0; c < (1 << copy_bits); ++c) sum += copies[(bin << copy_bits) + c];
-            }
-            lh[bin + (bin >> 6)] = sum;
-        }
-        __syncthreads();
-        // the bin that holds the want-th largest key, in two levels: the total of each chunk of 64 bins, the
-        // chunk from the top, then the bin inside it
-        if (tid < 64) {
-            uint32_t cs = 0;                                                // lane l: chunk 63 - l, from the top
-#pragma unroll 16
-            for (int i = 0; i < 64; ++i) cs += lh[(63 - lane) * 65 + i];
-            const uint32_t above = wave_incl_scan(cs) - cs;
-            const uint64_t who = __ballot(above < want && want <= above + cs);
-            const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
-            const uint32_t chunk = 63u - (uint32_t)src;
-            const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
-            const uint32_t bs = lh[chunk * 65 + (63 - lane)];               // lane l: bin 63 - l of the chunk
-            const uint32_t above2 = wave_incl_scan(bs) - bs;
-            const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
-            const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
-            if (lane == src2) { chosen[0] = chunk * 64 + (63u - (uint32_t)src2); chosen[1] = want2 - above2; }
-        }
-        __syncthreads();
-        hi = pass == 0 ? chosen[0] : ((hi << 12) | chosen[0]);
-        want = chosen[1];
-    }
-    const uint32_t thr = hi, take = want;        // the k-th largest key, and how many tiles equal to it are taken
+    }, L, &thr, &take, &equal);
 
-    // Keys equal to thr are taken in index order until `take` are used up, so every group needs the number of
-    // equal keys before it: lane r keeps the count of the wavefront's r-th group, wavefront 0 scans the groups.
-    uint32_t my_eq = 0;
-#pragma unroll
-    for (int r = 0; r < KPT; ++r) {
-        const uint32_t ne = (uint32_t)__popcll(__ballot(in_unit(r) && key[r] == thr));
-        if (lane == r) my_eq = ne;
-    }
-    if (lane < KPT) grp_eq[KPT * wave + lane] = my_eq;
-    __syncthreads();
-    constexpr int PER = NG / 64;                 // lane l of wavefront 0 scans the PER consecutive groups PER*l ..
-    if (tid < 64) {
-        uint32_t e[PER], esum = 0;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) { e[i] = grp_eq[lane * PER + i]; esum += e[i]; }
-        uint32_t eq_before = wave_incl_scan(esum) - esum;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) { grp_eq[lane * PER + i] = eq_before; eq_before += e[i]; }
-    }
-    __syncthreads();
-    // the width bit of every tile; lane r keeps the bit map word and the count of the wavefront's r-th group
-    const uint32_t my_eq_before = lane < KPT ? grp_eq[KPT * wave + lane] : 0u;
+    // The width bit of every tile; lane r keeps the bit map word of the wavefront's r-th group.
     uint64_t my_word = 0;
+    if (take == equal) {
+        // every tile whose key equals the threshold is taken (one such tile, as a rule)
 #pragma unroll
-    for (int r = 0; r < KPT; ++r) {
-        const bool ok = in_unit(r);
-        const bool eq = ok && key[r] == thr;
-        const uint64_t eqm = __ballot(eq);
-        bool sel = ok && key[r] > thr;
-        if (eqm) {                               // rare: at most a few groups hold keys equal to the threshold
-            const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)my_eq_before, r);
-            sel = sel || (eq && eq_before + (uint32_t)__popcll(eqm & below) < take);
+        for (int r = 0; r < KPT; ++r) {
+            const bool sel = in_unit(r) && key[r] >= thr;
+            const uint64_t selm = __ballot(sel);
+            if (lane == r) my_word = selm;
+            if (!aligned && in_unit(r)) sel_bytes[(uint64_t)u * n + (uint64_t)(KPT * wave + r) * 64u + lane] = sel ? 1 : 0;
         }
-        const uint64_t selm = __ballot(sel);
-        if (lane == r) my_word = selm;
-        if (!aligned && ok) sel_bytes[(uint64_t)u * n + (uint64_t)(KPT * wave + r) * 64u + lane] = sel ? 1 : 0;
+    } else {
+        // Keys equal to thr are taken in index order until `take` are used up, so every group needs the number of
+        // equal keys before it: lane r keeps the count of the wavefront's r-th group, wavefront 0 scans the groups.
+        uint32_t my_eq = 0;
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const uint32_t ne = (uint32_t)__popcll(__ballot(in_unit(r) && key[r] == thr));
+            if (lane == r) my_eq = ne;
+        }
+        if (lane < KPT) grp_eq[KPT * wave + lane] = my_eq;
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t e[PER], esum = 0;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) { e[i] = grp_eq[lane * PER + i]; esum += e[i]; }
+            uint32_t eq_before = wave_incl_scan(esum) - esum;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) { grp_eq[lane * PER + i] = eq_before; eq_before += e[i]; }
+        }
+        __syncthreads();
+        const uint32_t my_eq_before = lane < KPT ? grp_eq[KPT * wave + lane] : 0u;
+#pragma unroll
+        for (int r = 0; r < KPT; ++r) {
+            const bool ok = in_unit(r);
+            const bool eq = ok && key[r] == thr;
+            const uint64_t eqm = __ballot(eq);
+            bool sel = ok && key[r] > thr;
+            if (eqm) {                           // at most a few groups hold keys equal to the threshold, as a rule
+                const uint32_t eq_before = (uint32_t)__builtin_amdgcn_readlane((int)my_eq_before, r);
+                sel = sel || (eq && eq_before + (uint32_t)__popcll(eqm & below) < take);
+            }
+            const uint64_t selm = __ballot(sel);
+            if (lane == r) my_word = selm;
+            if (!aligned && ok) sel_bytes[(uint64_t)u * n + (uint64_t)(KPT * wave + r) * 64u + lane] = sel ? 1 : 0;
+        }
     }
     if (lane < KPT) grp_sel[KPT * wave + lane] = (uint32_t)__popcll(my_word);
     __syncthreads();
@@ -598,84 +663,8 @@ __global__ __launch_bounds__(kSmallUnitThreads) void k_select_small(const float 
 // (One launch, with the last workgroup of every unit doing the second part, measured ten times slower: what a
 // workgroup wrote becomes visible to a workgroup on another XCD only through fences that write back the L2.)
 
-constexpr uint32_t kFusedThreads = 1024;
+constexpr uint32_t kFusedThreads = kBlockSelectThreads;
 constexpr uint32_t kFusedKeysPerBlock = 16 * kFusedThreads;
-
-// Workgroup-wide radix select over the values that `each` hands to its argument (every thread visits its own share
-// of the values; each(g) calls g(value) for each of them): the `want`-th largest value (1 <= want <= number of values)
-// and how many values equal to it belong to the `want` largest.  The values of one selection lie close together
-// (the keys of one histogram bin), so the digits are taken from value - minimum: 12 bits at a time from the top of
-// max - min, usually two passes.  Called by all 1024 threads; `copies` (uint32[8192]), `lh` (uint32[4096 + 64]) and
-// `chosen` (uint32[4]) are LDS scratch; the result is the same in every thread.
-template <class Each>
-__device__ __forceinline__ void block_radix_select(uint32_t want, Each each, uint32_t *copies, uint32_t *lh,
-                                                   uint32_t *chosen, uint32_t *thr_out, uint32_t *take_out)
-{
-    constexpr int kBins = 4096;
-    const int tid = threadIdx.x, lane = tid & 63;
-    if (tid == 0) { chosen[2] = 0xffffffffu; chosen[3] = 0u; }
-    __syncthreads();
-    {
-        uint32_t lo = 0xffffffffu, hi = 0u;
-        each([&](uint32_t val) { lo = val < lo ? val : lo; hi = val > hi ? val : hi; });
-        // per wavefront first: a thousand atomics on one LDS address would take longer than the rest of the selection
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, off, 64), ohi = (uint32_t)__shfl_xor((int)hi, off, 64);
-            lo = olo < lo ? olo : lo;
-            hi = ohi > hi ? ohi : hi;
-        }
-        if (lane == 0 && lo <= hi) { atomicMin(&chosen[2], lo); atomicMax(&chosen[3], hi); }
-    }
-    __syncthreads();
-    const uint32_t vmin = chosen[2], span = chosen[3] - vmin;
-    int bits = 32 - __builtin_clz(span | 1u);    // digits cover bits [0, bits) of value - vmin
-    uint32_t prefix = 0;                         // the digits found so far, as the top bits of value - vmin
-    // two copies of every bin, indexed by the lane: a wavefront's atomics on one LDS address are serialized
-    const uint32_t my_copy = (uint32_t)lane & 1u;
-#pragma unroll 1
-    while (true) {
-        const int shift = bits > 12 ? bits - 12 : 0;         // this pass: bits [shift, bits)
-        const uint32_t mask = (1u << (bits - shift)) - 1u;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) copies[i * (int)kFusedThreads + tid] = 0;
-        __syncthreads();
-        each([&](uint32_t val) {
-            const uint32_t d = val - vmin;
-            if (bits == 32 || (d >> bits) == prefix) atomicAdd(&copies[(((d >> shift) & mask) << 1) | my_copy], 1u);
-        });
-        __syncthreads();
-#pragma unroll
-        for (int part = 0; part < kBins / (int)kFusedThreads; ++part) {
-            const uint32_t bin = (uint32_t)tid + kFusedThreads * part;
-            lh[bin + (bin >> 6)] = bin <= mask ? copies[2 * bin] + copies[2 * bin + 1] : 0u;
-        }
-        __syncthreads();
-        if (tid < 64) {
-            uint32_t cs = 0;                                                // lane l: chunk 63 - l of 64 bins, from the top
-#pragma unroll 16
-            for (int i = 0; i < 64; ++i) cs += lh[(63 - lane) * 65 + i];
-            const uint32_t above = wave_incl_scan(cs) - cs;
-            const uint64_t who = __ballot(above < want && want <= above + cs);
-            const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
-            const uint32_t chunk = 63u - (uint32_t)src;
-            const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
-            const uint32_t bs = lh[chunk * 65 + (63 - lane)];
-            const uint32_t above2 = wave_incl_scan(bs) - bs;
-            const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
-            const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
-            if (lane == src2) { chosen[0] = chunk * 64 + (63u - (uint32_t)src2); chosen[1] = want2 - above2; }
-        }
-        __syncthreads();
-        prefix = (bits - shift == 32) ? chosen[0] : ((prefix << (bits - shift)) | chosen[0]);
-        want = chosen[1];
-        __syncthreads();
-        if (shift == 0) break;
-        bits = shift;
-    }
-    *thr_out = vmin + prefix;
-    *take_out = want;
-}
 
 __global__ __launch_bounds__(kFusedThreads) void k_select_classify(const float *__restrict__ H, uint32_t n, uint32_t k,
                                                                    float bin_scale,
@@ -753,9 +742,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_select_classify(const float *
 
 // LDS of k_select_resolve
 struct ResolveLds {
-    uint32_t copies[8192];
-    uint32_t lh[4096 + 64];
-    uint32_t chosen[4];
+    BlockSelectLds sel;
+    uint32_t chosen[2];
     uint32_t n_equal, n_before;
     uint32_t equal_tile[kFusedThreads];          // tiles whose key equals the threshold (the first 1024)
     uint32_t wave_total[kFusedThreads / 64];
@@ -770,9 +758,13 @@ __device__ __forceinline__ void rank_candidates(uint32_t rem, EachCandidate each
 {
     const int tid = threadIdx.x;
     if (tid == 0) L.n_equal = 0;
-    uint32_t thr, take;
-    block_radix_select(rem, [&](auto g) { each_candidate([&](uint32_t key, uint32_t) { g(key); }); }, L.copies, L.lh,
-                       L.chosen, &thr, &take);
+    uint32_t thr, take, equal;
+    block_radix_select(rem, [&](auto g) { each_candidate([&](uint32_t key, uint32_t) { g(key); }); }, L.sel, &thr, &take,
+                       &equal);
+    if (take == equal) {                         // every tile equal to the threshold is taken (one, as a rule)
+        each_candidate([&](uint32_t key, uint32_t tile) { if (key >= thr) take_it(tile); });
+        return;
+    }
     // tiles above the threshold are taken; of those equal to it, the `take` with the lowest tile indices
     each_candidate([&](uint32_t key, uint32_t tile) {
         if (key > thr) take_it(tile);
@@ -792,10 +784,10 @@ __device__ __forceinline__ void rank_candidates(uint32_t rem, EachCandidate each
             if (lower < take) take_it(mine);
         }
     } else {
-        uint32_t thr_index, unused;              // a tile with key == thr is taken iff ~tile >= thr_index
+        uint32_t thr_index, unused, unused2;     // a tile with key == thr is taken iff ~tile >= thr_index
         block_radix_select(take, [&](auto g) {
             each_candidate([&](uint32_t key, uint32_t tile) { if (key == thr) g(~tile); });
-        }, L.copies, L.lh, L.chosen, &thr_index, &unused);
+        }, L.sel, &thr_index, &unused, &unused2);
         each_candidate([&](uint32_t key, uint32_t tile) { if (key == thr && ~tile >= thr_index) take_it(tile); });
     }
 }
