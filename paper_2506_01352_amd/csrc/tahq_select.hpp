@@ -1,22 +1,24 @@
 // Top-p% tile selection (Sec. 3.2): inside every ranking unit the k (allocation) tiles of highest entropy get
-// the wider code (4 bits by default), ties going to the lower tile index.  Exact, deterministic, no sort:
+// the wider code (4 bits by default), ties going to the lower tile index.  Exact, deterministic, no sort.
+// Entropies map to order-preserving 32-bit keys; three ways to find the k-th largest key K*, how many tiles equal to
+// K* are still wanted (`take`), and from them the bit map and the rank table:
 //
-//   * entropies map to order-preserving 32-bit keys;
-//   * three histogram passes (10 + 11 + 11 bits, from the top; the first one is normally folded into
-//     the entropy kernel) find the k-th largest key K*
-//     and how many tiles equal to K* are still wanted (`take`);
-//   * per segment of tiles, counts of keys == K* and > K* ; their prefix sums give every tile
-//     its place among the equal keys (index order) and every 64-tile group its rank-table entry.
-//
-// Ranking units of at most 32768 tiles skip all of this: k_select_small ranks such a unit with one workgroup in one
-// launch (keys in registers, histograms in LDS), because at that size the five launches cost more than the work.
+//   * ranking units of at most 32768 tiles: k_select_small, one workgroup per unit in one launch (keys in registers,
+//     radix passes on an LDS histogram), because at that size several launches cost more than the work;
+//   * larger units that start on 64-tile boundaries and are whole batches of the entropy kernel: that kernel also
+//     counts the entropies over 2048 linear bins per unit; k_select_classify settles every tile outside the bin that
+//     holds K* and lists the tiles inside it, k_select_resolve ranks that list (further down in this file);
+//   * everything else, and every unit when the caller forces it: three histogram passes (10 + 11 + 11 bits, from the
+//     top; the first one folded into the entropy kernel where units are whole batches) find K* and `take`; then, per
+//     segment of tiles, counts of keys == K* and > K*, whose prefix sums give every tile its place among the equal keys
+//     (index order) and every 64-tile group its rank-table entry: k_radix_pass x 2, k_seg_count, k_assign.
 //
 // Kernels never wait on each other inside a launch: every dependency is a launch boundary, and the
 // small reductions a later kernel needs (which bin holds the k-th key, prefix over segments) are
 // recomputed by every block from a few KB of global data.
 //
-// Histograms of digits 1 and 2 are kept in two levels so that no address takes more than a handful of
-// global atomics: every workgroup stores its own 2048-bin histogram with plain stores and adds only the
+// In the third way the histograms of digits 1 and 2 are kept in two levels so that no address takes more than a handful
+// of global atomics: every workgroup stores its own 2048-bin histogram with plain stores and adds only the
 // totals of its 64 super-bins (32 bins each) atomically.  The reader picks the super-bin from the 64
 // totals, then sums the workgroups' counts for the 32 bins inside it.
 #pragma once
