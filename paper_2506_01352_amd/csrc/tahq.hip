@@ -407,9 +407,15 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
     for (int i = 0; i < 5; ++i) { pads.begin[i] = sec_begin[i]; pads.len[i] = (uint32_t)(sec_end[i] - sec_begin[i]); }
     const bool histograms = select && !small_units;
     const uint32_t zero_words = histograms ? (uint32_t)(ws.zero_bytes / 4) : 0u;
-    if (phases & TAHQ_PHASE_PROLOGUE)
-        q(k_prologue, dim3(histograms ? 32 : 1), dim3(256), packed, hdr, pads,
-                           reinterpret_cast<uint32_t *>(wsb + ws.hist0), zero_words);
+    // a tensor whose tiles all have the same width needs no selection: its bit map and rank table are constants, which
+    // the prologue writes as well when the caller asks for both phases at once
+    const bool const_in_prologue = !select && (phases & TAHQ_PHASE_PROLOGUE) && (phases & TAHQ_PHASE_SELECT);
+    if (phases & TAHQ_PHASE_PROLOGUE) {
+        const uint32_t const_words = const_in_prologue ? (uint32_t)words64 : 0u;
+        const uint32_t blocks = histograms ? 32u : (const_words ? (blocks_for(words64) < 256u ? blocks_for(words64) : 256u) : 1u);
+        q(k_prologue, dim3(blocks), dim3(256), packed, hdr, pads, reinterpret_cast<uint32_t *>(wsb + ws.hist0), zero_words,
+          const_words, (uint32_t)s.T, s.kA == s.nA ? 1 : 0, bitmap, ranks);
+    }
 
     if (select) {
         float *H = reinterpret_cast<float *>(wsb + ws.keys);
@@ -490,7 +496,7 @@ tahq_status tahq_encode_phases(const tahq_config *cfg, const void *d_in, void *d
                 q(k_bitmap_pack, dim3(blocks_for(words64 * 64)), dim3(256),
                                    (const uint8_t *)sel, (uint32_t)s.T, bitmap);
         }
-    } else if (phases & TAHQ_PHASE_SELECT) {
+    } else if ((phases & TAHQ_PHASE_SELECT) && !const_in_prologue) {
         q(k_bitmap_const, dim3(blocks_for(words64)), dim3(256), (uint32_t)s.T,
                            s.kA == s.nA ? 1 : 0, bitmap, ranks);
     }

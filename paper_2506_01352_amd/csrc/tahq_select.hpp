@@ -932,28 +932,36 @@ __global__ __launch_bounds__(kFusedThreads) void k_select_resolve(const float *_
     }
 }
 
-// Budget 3.0 or 4.0: every tile has the same width.
-__global__ __launch_bounds__(256) void k_bitmap_const(uint32_t T, int all4, uint64_t *__restrict__ bitmap,
-                                                      uint32_t *__restrict__ ranks)
+// A budget of exactly `lo` or `lo + 1` bits: every tile has the same width.  Bit map word and rank-table entry `w`.
+__device__ __forceinline__ void constant_width_word(uint64_t w, uint32_t T, int all_wide, uint64_t *__restrict__ bitmap,
+                                                    uint32_t *__restrict__ ranks)
 {
-    const uint64_t w = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    const uint64_t words = ((uint64_t)T + 63) / 64;
-    if (w >= words) return;
     uint64_t bits = 0;
-    if (all4) {
+    if (all_wide) {
         const uint64_t left = (uint64_t)T - w * 64;
         bits = left >= 64 ? ~0ull : ((1ull << left) - 1ull);
     }
     bitmap[w] = bits;
-    ranks[w] = all4 ? (uint32_t)(w * 64) : 0u;
+    ranks[w] = all_wide ? (uint32_t)(w * 64) : 0u;
+}
+
+__global__ __launch_bounds__(256) void k_bitmap_const(uint32_t T, int all_wide, uint64_t *__restrict__ bitmap,
+                                                      uint32_t *__restrict__ ranks)
+{
+    const uint64_t w = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (w < ((uint64_t)T + 63) / 64) constant_width_word(w, T, all_wide, bitmap, ranks);
 }
 
 // Header, zeroed section padding, zeroed histograms.
 struct HeaderWords { uint32_t w[16]; };
 struct PadList { uint64_t begin[5]; uint32_t len[5]; };
 
+// With `const_words` != 0 it also writes the bit map and the rank table of a tensor whose tiles all have the same width
+// (what k_bitmap_const does in a launch of its own).
 __global__ __launch_bounds__(256) void k_prologue(uint8_t *__restrict__ packed, HeaderWords hdr, PadList pads,
-                                                  uint32_t *__restrict__ zero_base, uint32_t zero_words)
+                                                  uint32_t *__restrict__ zero_base, uint32_t zero_words,
+                                                  uint32_t const_words, uint32_t T, int all_wide,
+                                                  uint64_t *__restrict__ bitmap, uint32_t *__restrict__ ranks)
 {
     const uint32_t gid = blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0) {
@@ -962,6 +970,7 @@ __global__ __launch_bounds__(256) void k_prologue(uint8_t *__restrict__ packed, 
             if (threadIdx.x < pads.len[s]) packed[pads.begin[s] + threadIdx.x] = 0;
     }
     for (uint32_t i = gid; i < zero_words; i += gridDim.x * 256) zero_base[i] = 0u;
+    for (uint32_t w = gid; w < const_words; w += gridDim.x * 256) constant_width_word(w, T, all_wide, bitmap, ranks);
 }
 
 }  // namespace tahq
