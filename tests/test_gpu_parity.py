@@ -348,6 +348,34 @@ def test_repeated_calls_are_deterministic_and_workspace_contents_do_not_matter(t
     assert np.array_equal(results[0], results[1]) and np.array_equal(results[1], results[2])
 
 
+def test_phase_by_phase_calls_write_the_same_stream(tahq):
+    # tahq_encode_phases, one phase per call, against the one call: uniform widths (the one call folds the constant
+    # bit map into its first kernel, a call for the selection phase alone writes it by itself), small ranking units,
+    # large ranking units
+    cases = [(3, dict(batch=2, seq=64), None), (3, dict(batch=2, seq=64), 4.0), (2, dict(batch=2, seq=64), None),
+             (4, dict(batch=1, seq=1024), None)]
+    for index, shape, budget in cases:
+        w, x = workloads.generate(index, **shape)
+        budget = w.budget_bits if budget is None else budget
+        _say(f"[case] phases one by one, {w.name} budget {budget}")
+        cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, budget)
+        d_in = to_device(x)
+        whole = Guarded(tahq.tahq_packed_size(cfg))
+        parts = Guarded(tahq.tahq_packed_size(cfg))
+        ws = Guarded(tahq.tahq_workspace_size(cfg))
+        ws.view.fill_(0x77)
+        tahq.tahq_encode(cfg, d_in, whole.view, ws.view)
+        ws.view.fill_(0x11)
+        for phase in (tahq.PHASE_PROLOGUE, tahq.PHASE_ENTROPY, tahq.PHASE_SELECT, tahq.PHASE_QUANT):
+            tahq.tahq_encode_phases(cfg, d_in, parts.view, ws.view, phase)
+        torch.cuda.synchronize()
+        for g in (whole, parts, ws):
+            g.check()
+        assert torch.equal(whole.view, parts.view)
+        ocfg = o32.make_cfg(w.batch, w.seq, w.hidden, w.tile, w.dtype, budget)
+        assert np.array_equal(whole.view.cpu().numpy(), o32.encode(ocfg, x))
+
+
 def test_side_stream(tahq):
     w, x = workloads.generate(2, batch=1, seq=64)
     cfg = tahq.make_config(w.batch, w.seq, w.hidden, w.tile, w.dtype, w.budget_bits)
