@@ -624,6 +624,45 @@ def test_decoding_a_damaged_stream_stays_inside_its_buffers(tahq, G, low):
             assert np.array_equal(packed.view.cpu().numpy(), host)     # the stream is only read
 
 
+def _large_unit_cases(count, seed):
+    """Ranking units above the single-launch limit that start on 64-tile boundaries (the two-launch selection from the
+    entropy kernel's histogram), with data that crowds or overflows the threshold bin."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        G = int(rng.choice([8, 16, 32, 64, 128]))
+        M = int(rng.choice([16, 32, 64, 128, 40, 24]))
+        S = int(rng.choice([512, 1024, 2048, 4096, 768, 1536]))
+        B = int(rng.choice([1, 2, 3]))
+        n = S * M
+        if n <= 32768 or n % 256 or B * n * G > 12_000_000:
+            continue
+        low = int(rng.choice([3, 3, 3, 2, 4]))
+        out.append(dict(B=B, S=S, M=M, G=G, dtype=int(rng.integers(0, 2)), low=low, scope=int(rng.random() < 0.2),
+                        budget=float(np.float32(low + rng.uniform(0.02, 0.98))), kind=len(out) % 4,
+                        seed=int(rng.integers(0, 2 ** 31))))
+    return out
+
+
+@pytest.mark.parametrize("c", _large_unit_cases(12, seed=5),
+                         ids=lambda c: "{B}x{S}x{M}_g{G}_d{dtype}_lo{low}_k{kind}_s{scope}".format(**c))
+def test_large_ranking_units_bit_exact(tahq, c):
+    rng = np.random.default_rng(c["seed"])
+    B, S, Cc, G = c["B"], c["S"], c["M"] * c["G"], c["G"]
+    x = rng.standard_normal((B, S, Cc)).astype(np.float32)
+    if c["kind"] == 1:      # seven distinct tiles: every entropy is tied thousands of times
+        proto = rng.standard_normal((7, G)).astype(np.float32)
+        x = proto[rng.integers(0, 7, size=(B, S, c["M"]))].reshape(B, S, Cc)
+    elif c["kind"] == 2:    # ties at entropy 0 and at ln G
+        x[:, ::3, :] = 0.0
+        x[:, 1::5, :] = 1.5
+    elif c["kind"] == 3:    # a narrow band of entropies: a crowded threshold bin
+        x = (1.0 + 1e-3 * rng.standard_normal((B, S, Cc))).astype(np.float32)
+    xin = x if c["dtype"] == 0 else workloads.f32_to_bf16_bits(x)
+    _say(f"[case] large ranking units {c}")
+    check_case(tahq, xin, B, S, Cc, G, c["dtype"], c["budget"], low_bits=c["low"], scope=c["scope"])
+
+
 def _random_configurations(count, seed):
     """Seeded sweep over the configuration space: tile width, dtype, widths, budget, allocation tile, scope,
     tau, shapes with ragged batches and ranking units on both sides of the single-launch threshold."""
