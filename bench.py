@@ -64,6 +64,25 @@ def stored_traffic(stem):
     return per_kernel, sum(per_kernel.values()), "profiles/" + name
 
 
+def stored_valu(stem):
+    """Vector-ALU instructions per tile and issue utilisation of every kernel of one step, from the rocprofv3 --pmc
+    summary under profiles/ (stored readings, like stored_traffic).  Returns (dict kernel -> (instructions per tile,
+    utilisation in per cent), file name) or (None, None)."""
+    name = stem + ".md"
+    path = os.path.join(PROFILES, name)
+    if not os.path.exists(path):
+        return None, None
+    per_kernel = {}
+    for line in open(path).read().splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 6 and cells[0].startswith("k_"):
+            try:
+                per_kernel[cells[0].split("<")[0]] = (float(cells[3]), float(cells[5].rstrip("% ")))
+            except ValueError:
+                continue
+    return (per_kernel, "profiles/" + name) if per_kernel else (None, None)
+
+
 def algorithmic_bytes(w, packed_size, T, select):
     """Bytes each kernel must move per launch (per-element figures x elements of one launch)."""
     del select
@@ -408,11 +427,16 @@ def main():
     storage = "bf16" if w.dtype else "f32"
     stem = f"cfg{args.config}_{storage}_{w.batch}x{w.seq}x{w.hidden}_g{w.tile}"
     traffic, step_traffic, traffic_src = stored_traffic("hbm_traffic_" + stem) if stock else (None, None, None)
+    valu, valu_src = stored_valu("valu_counters_" + stem) if stock else (None, None)
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic.get(dominant) if traffic else None,
         "traffic_source": traffic_src,
         "algorithmic_bytes_per_launch": alg[dominant], "avg_launch_ms": dom_ms, "launches_timed": len(evs),
+        # the co-bound: vector-ALU instructions per tile and issue utilisation of the same kernel (stored readings)
+        "valu_instructions_per_tile": valu[dominant][0] if valu and dominant in valu else None,
+        "valu_issue_utilisation_pct": valu[dominant][1] if valu and dominant in valu else None,
+        "valu_source": valu_src,
     }
     # bytes the method must move: the tensor in, the stream out, the stream in, the tensor out
     must_move = 2 * nbytes + 2 * packed_size

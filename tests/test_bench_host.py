@@ -77,3 +77,10 @@ def test_stored_counter_readings_come_from_the_profile_summaries():
     naive, _, nsrc = bench.stored_traffic("hbm_traffic_naive_cfg5_bf16_16x2048x5120_b8")
     assert nsrc and abs(naive["k_naive_encode"] / 503316544 - 1.0) < 0.02
     assert bench.stored_traffic("hbm_traffic_no_such_workload") == (None, None, None)
+    # the vector-ALU readings of the same workload: instructions per tile and issue utilisation per kernel
+    valu, vsrc = bench.stored_valu("valu_counters_cfg4_bf16_8x4096x8192_g64")
+    assert vsrc == "profiles/valu_counters_cfg4_bf16_8x4096x8192_g64.md"
+    for kernel in ("k_entropy", "k_quant_pack", "k_decode"):
+        per_tile, pct = valu[kernel]
+        assert 300 < per_tile < 1500 and 30 < pct < 130, (kernel, per_tile, pct)
+    assert bench.stored_valu("valu_counters_no_such_workload") == (None, None)
