@@ -33,6 +33,7 @@ constexpr uint32_t kHistBins = 2048;      // bins of radix digits 1 and 2 (11 bi
 constexpr uint32_t kDigit0Bins = 1024;    // bins of radix digit 0 (key bits 31..22)
 constexpr uint32_t kRadixKeysPerBlock = 8192;
 constexpr uint32_t kLinBins = 2048;       // bins of the entropy histogram of the single-launch selection of large units
+constexpr uint32_t kSubBins = 1024;       // sub-bins of the bin that holds the threshold (k_select_resolve)
 constexpr uint32_t kCandCap = 16384;      // tiles of the threshold bin that the selection keeps in a list, per ranking unit
 
 struct Workspace {
@@ -167,6 +168,19 @@ __device__ __forceinline__ uint32_t order_key(float h)
 __device__ __forceinline__ uint32_t linear_bin(float h, float scale)
 {
     return (uint32_t)__builtin_amdgcn_fmed3f(h * scale, 0.0f, (float)(kLinBins - 1));
+}
+
+// Sub-bin of an entropy that lies in linear bin `b`, 0 .. kSubBins - 1: non-decreasing in the entropy.  h * scale is
+// the product linear_bin rounds down; its distance to b is exact in fp32, and so is the multiplication by a power of two.
+__device__ __forceinline__ uint32_t linear_sub_bin(float h, float scale, uint32_t b)
+{
+    return (uint32_t)__builtin_amdgcn_fmed3f((h * scale - (float)b) * (float)kSubBins, 0.0f, (float)(kSubBins - 1));
+}
+
+// The entropy an order-preserving key was made from.
+__device__ __forceinline__ float key_to_float(uint32_t key)
+{
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
 // fp32(1/sqrt(G)), the normalisation of Eq. 4.

@@ -745,7 +745,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_select_classify(const float *
 // LDS of k_select_resolve
 struct ResolveLds {
     BlockSelectLds sel;
-    uint32_t chosen[2];
+    uint32_t chosen[4];                          // threshold bin, wanted inside it; threshold sub-bin, wanted inside it
     uint32_t n_equal, n_before;
     uint32_t equal_tile[kFusedThreads];          // tiles whose key equals the threshold (the first 1024)
     uint32_t wave_total[kFusedThreads / 64];
@@ -889,7 +889,10 @@ __global__ __launch_bounds__(kFusedThreads) void k_select_resolve(const float *_
         pick_bin<kLinBins>(lin_hist + (uint64_t)u * kLinBins, k, &bin, &rem);
         if (lane == 0) { L.chosen[0] = bin; L.chosen[1] = rem; }
     }
-    if (tid == 0) L.n_before = 0;
+    if (tid == 0) { L.n_before = 0; L.n_equal = 0; }
+    static_assert(kSubBins == kFusedThreads, "one sub-bin per thread");
+    uint32_t *sub_hist = L.sel.copies;           // the threshold bin's candidates by sub-bin
+    sub_hist[tid] = 0;
     if ((uint32_t)tid < GROUPS) { L.words[2 * tid] = (uint32_t)my_word; L.words[2 * tid + 1] = (uint32_t)(my_word >> 32); }
     __syncthreads();
     const uint32_t bstar = L.chosen[0], rem = L.chosen[1];
@@ -902,15 +905,64 @@ __global__ __launch_bounds__(kFusedThreads) void k_select_resolve(const float *_
     // the selected candidates: those of my block go into its words, those before it are counted
     const uint32_t first_tile = group0 * 64u;
     uint32_t before = 0;
+    auto take_it = [&](uint32_t tile) {
+        if (tile < first_tile) ++before;
+        else if (tile - first_tile < kFusedKeysPerBlock) atomicOr(&L.words[(tile - first_tile) >> 5], 1u << (tile & 31u));
+    };
     if (rem != 0) {
-        rank_candidates(rem, [&](auto f) {
+        // A histogram of the candidates over 1024 sub-bins of their bin narrows the threshold down once more:
+        // candidates in a higher sub-bin are selected, those in the threshold's own sub-bin (a handful, as a rule) are
+        // ranked directly, thread t placing the t-th of them among all of them by (key descending, tile ascending).
+        uint32_t sub[CPT];
 #pragma unroll
-            for (int r = 0; r < CPT; ++r)
-                if ((uint32_t)r * kFusedThreads + tid < listed) f(c[r].x, c[r].y);
-        }, [&](uint32_t tile) {
-            if (tile < first_tile) ++before;
-            else if (tile - first_tile < kFusedKeysPerBlock) atomicOr(&L.words[(tile - first_tile) >> 5], 1u << (tile & 31u));
-        }, L);
+        for (int r = 0; r < CPT; ++r) {
+            sub[r] = 0xffffffffu;
+            if ((uint32_t)r * kFusedThreads + tid < listed) {
+                sub[r] = linear_sub_bin(key_to_float(c[r].x), bin_scale, bstar);
+                atomicAdd(&sub_hist[sub[r]], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t s, r2;
+            pick_bin<kSubBins>(sub_hist, rem, &s, &r2);
+            if (lane == 0) { L.chosen[2] = s; L.chosen[3] = r2; }
+        }
+        __syncthreads();
+        const uint32_t sstar = L.chosen[2], rem2 = L.chosen[3];
+        uint32_t *list_key = L.sel.copies + kSubBins, *list_tile = L.equal_tile;
+        uint32_t in_sub = 0;                     // bit r: my r-th candidate lies in the threshold's sub-bin
+#pragma unroll
+        for (int r = 0; r < CPT; ++r) {
+            if (sub[r] != 0xffffffffu) {
+                if (sub[r] > sstar) take_it(c[r].y);
+                else if (sub[r] == sstar) {
+                    in_sub |= 1u << r;
+                    const uint32_t at = atomicAdd(&L.n_equal, 1u);
+                    if (at < kFusedThreads) { list_key[at] = c[r].x; list_tile[at] = c[r].y; }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t nl = L.n_equal;
+        if (nl <= kFusedThreads) {
+            if ((uint32_t)tid < nl) {
+                const uint32_t key = list_key[tid], tile = list_tile[tid];
+                uint32_t ahead = 0;
+                for (uint32_t i = 0; i < nl; ++i) {
+                    const uint32_t ki = list_key[i];
+                    ahead += (ki > key || (ki == key && list_tile[i] < tile)) ? 1u : 0u;
+                }
+                if (ahead < rem2) take_it(tile);
+            }
+        } else {
+            __syncthreads();                     // the list is dropped: its memory serves the radix select
+            rank_candidates(rem2, [&](auto f) {
+#pragma unroll
+                for (int r = 0; r < CPT; ++r)
+                    if ((in_sub >> r) & 1u) f(c[r].x, c[r].y);
+            }, take_it, L);
+        }
     }
     above_before += before;
 #pragma unroll
