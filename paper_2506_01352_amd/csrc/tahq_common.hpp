@@ -163,18 +163,23 @@ __device__ __forceinline__ uint32_t order_key(float h)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Linear bin of an entropy, 0 .. kLinBins - 1: non-decreasing in the entropy (so a higher bin means a higher rank),
-// and the same instruction sequence wherever it is evaluated.  Negative values and NaN go to bin 0.
+// Linear bin of an entropy, 0 .. kLinBins - 1: non-decreasing in the entropy's order-preserving key (so a higher bin
+// means a higher rank), and the same instruction sequence wherever it is evaluated.  Negative values go to bin 0; a NaN
+// goes where its key goes: above +infinity with the sign bit clear, below -infinity with it set.
 __device__ __forceinline__ uint32_t linear_bin(float h, float scale)
 {
-    return (uint32_t)__builtin_amdgcn_fmed3f(h * scale, 0.0f, (float)(kLinBins - 1));
+    // the median of three takes a NaN for the smallest of the three (bin 0, where a NaN with the sign bit set belongs)
+    const uint32_t b = (uint32_t)__builtin_amdgcn_fmed3f(h * scale, 0.0f, (float)(kLinBins - 1));
+    return (int32_t)__float_as_uint(h) > 0x7f800000 ? kLinBins - 1 : b;
 }
 
-// Sub-bin of an entropy that lies in linear bin `b`, 0 .. kSubBins - 1: non-decreasing in the entropy.  h * scale is
-// the product linear_bin rounds down; its distance to b is exact in fp32, and so is the multiplication by a power of two.
+// Sub-bin of an entropy that lies in linear bin `b`, 0 .. kSubBins - 1: non-decreasing in the entropy's key.  h * scale
+// is the product linear_bin rounds down; its distance to b is exact in fp32, and so is the multiplication by a power of
+// two.
 __device__ __forceinline__ uint32_t linear_sub_bin(float h, float scale, uint32_t b)
 {
-    return (uint32_t)__builtin_amdgcn_fmed3f((h * scale - (float)b) * (float)kSubBins, 0.0f, (float)(kSubBins - 1));
+    const uint32_t s = (uint32_t)__builtin_amdgcn_fmed3f((h * scale - (float)b) * (float)kSubBins, 0.0f, (float)(kSubBins - 1));
+    return (int32_t)__float_as_uint(h) > 0x7f800000 ? kSubBins - 1 : s;
 }
 
 // The entropy an order-preserving key was made from.

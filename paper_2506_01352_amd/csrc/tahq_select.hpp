@@ -423,6 +423,28 @@ struct BlockSelectLds {
     uint32_t chosen[5];                          // bin, wanted inside it, its count; smallest and largest value
 };
 
+// Run by the first wavefront: the bin of L.lh that holds the `want`-th largest value, in two levels -- the chunk of 64
+// bins from the top (totals in L.chunk_total; chunks that are not in use hold 0), then the bin inside it.  Leaves the
+// bin, the number still wanted inside it and its count in L.chosen[0..2].
+__device__ __forceinline__ void pick_from_chunks(BlockSelectLds &L, uint32_t want, int lane)
+{
+    const uint32_t cs = L.chunk_total[63 - lane];                           // lane l: chunk 63 - l, from the top
+    const uint32_t above = wave_incl_scan(cs) - cs;
+    const uint64_t who = __ballot(above < want && want <= above + cs);
+    const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
+    const uint32_t chunk = 63u - (uint32_t)src;
+    const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
+    const uint32_t bs = L.lh[chunk * 65 + (63 - lane)];                     // lane l: bin 63 - l of the chunk
+    const uint32_t above2 = wave_incl_scan(bs) - bs;
+    const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
+    const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
+    if (lane == src2) {
+        L.chosen[0] = chunk * 64 + (63u - (uint32_t)src2);
+        L.chosen[1] = want2 - above2;
+        L.chosen[2] = bs;
+    }
+}
+
 // Workgroup-wide radix select over the values that `each` hands to its argument (every thread visits its own share
 // of the values; each(g) calls g(value) for each of them): the `want`-th largest value (1 <= want <= number of values),
 // how many values equal to it belong to the `want` largest, and how many values equal to it there are.  The values of
@@ -485,24 +507,7 @@ __device__ __forceinline__ void block_radix_select(uint32_t want, Each each, Blo
             if (lane == 63) L.chunk_total[(kBlockSelectThreads / 64) * part + wave] = upto;
         }
         __syncthreads();
-        // the bin that holds the want-th largest value, in two levels: the chunk from the top, then the bin inside it
-        if (tid < 64) {
-            const uint32_t cs = L.chunk_total[63 - lane];                   // lane l: chunk 63 - l, from the top
-            const uint32_t above = wave_incl_scan(cs) - cs;
-            const uint64_t who = __ballot(above < want && want <= above + cs);
-            const int src = who ? (int)__ffsll((unsigned long long)who) - 1 : 0;
-            const uint32_t chunk = 63u - (uint32_t)src;
-            const uint32_t want2 = want - (uint32_t)__shfl((int)above, src, 64);
-            const uint32_t bs = L.lh[chunk * 65 + (63 - lane)];             // lane l: bin 63 - l of the chunk
-            const uint32_t above2 = wave_incl_scan(bs) - bs;
-            const uint64_t who2 = __ballot(above2 < want2 && want2 <= above2 + bs);
-            const int src2 = who2 ? (int)__ffsll((unsigned long long)who2) - 1 : 0;
-            if (lane == src2) {
-                L.chosen[0] = chunk * 64 + (63u - (uint32_t)src2);
-                L.chosen[1] = want2 - above2;
-                L.chosen[2] = bs;
-            }
-        }
+        if (tid < 64) pick_from_chunks(L, want, lane);
         __syncthreads();
         prefix = (bits - shift == 32) ? L.chosen[0] : ((prefix << (bits - shift)) | L.chosen[0]);
         want = L.chosen[1];

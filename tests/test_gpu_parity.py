@@ -588,6 +588,36 @@ def test_nan_inf_and_huge_inputs_are_lossy_but_never_a_fault(tahq):
         assert np.array_equal(out[n * G:].view(np.uint32), want_out.view(np.uint32))
 
 
+def test_non_finite_entropies_in_large_ranking_units_follow_key_order(tahq):
+    # NaN and infinite inputs give NaN entropies; the selection orders tiles by their entropies' order-preserving keys,
+    # where a NaN with the sign bit clear sorts above +infinity.  The two-launch selection of large units (bins of
+    # the entropy) and the multi-launch radix select (digits of the key) must agree on such a tensor too; run_gpu
+    # compares their streams.  The clean sample is checked against the oracle.
+    rng = np.random.default_rng(19)
+    G, S, M = 32, 1024, 64                          # 65536 tiles per sample: above the single-launch limit
+    x = rng.standard_normal((2, S, M * G)).astype(np.float32)
+    clean = x[1:2].copy()
+    x[0, 0, 3] = np.nan
+    x[0, 7, 70] = np.inf
+    x[0, 9, 130] = -np.inf
+    x[0, 100:140, 64:128] = np.nan
+    x[0, 200:260, :32] = 3e38
+    x[0, 300:310, :] = 0.0
+    for budget in (3.02, 3.5, 3.98):
+        _say(f"[case] non-finite inputs, large ranking units, budget {budget}")
+        cfg = tahq.make_config(2, S, M * G, G, tahq.F32, budget)
+        H, packed, out = run_gpu(tahq, cfg, x, tahq.F32)
+        ocfg1 = o32.make_cfg(1, S, M * G, G, tahq.F32, budget)
+        want = o32.encode(ocfg1, clean)
+        n, k = S * M, o32.k_per_unit(ocfg1)
+        off2 = o64.section_offsets(2 * n, G, 2, k)
+        off1 = o64.section_offsets(n, G, 1, k)
+        assert np.array_equal(packed[off2["bitmap"] + n // 8: off2["bitmap"] + 2 * n // 8],
+                              want[off1["bitmap"]: off1["bitmap"] + n // 8])
+        pay1 = (G // 8) * (3 * n + k)
+        assert np.array_equal(packed[off2["payload"] + pay1: off2["total"]], want[off1["payload"]: off1["total"]])
+
+
 @pytest.mark.parametrize("G,low", [(64, 3), (32, 2), (8, 3), (128, 3), (16, 2), (64, 7), (16, 5), (128, 1)])
 def test_decoding_a_damaged_stream_stays_inside_its_buffers(tahq, G, low):
     # The decoder clamps the rank table to the number of wide tiles the configuration implies, ignores a decreasing
