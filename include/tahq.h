@@ -155,14 +155,16 @@ tahq_status tahq_encode_noalloc(const tahq_config *cfg, const void *d_in,
 /* The encoder's phases, in the order they run.  tahq_encode runs all of them. */
 enum {
     TAHQ_PHASE_PROLOGUE = 1,   /* header, section padding, cleared selection scratch          */
-    TAHQ_PHASE_ENTROPY = 2,    /* Eq. 1-2 for every tile (skipped when budget is 3.0 or 4.0)  */
+    TAHQ_PHASE_ENTROPY = 2,    /* Eq. 1-2 for every tile (skipped when every tile gets one width) */
     TAHQ_PHASE_SELECT = 4,     /* top-p% selection: bit map and rank table     [Sec. 3.2]     */
     TAHQ_PHASE_QUANT = 8,      /* Eq. 3-4, quantize, pack                      [Sec. 3.3-3.4] */
     TAHQ_PHASE_ALL = 15,
-    /* Not a phase but an option, OR-ed into `phases`: rank even small ranking units (up to 32768
-     * tiles, which one workgroup ranks in a single launch by default) with the general multi-launch
-     * selection.  Same result; meant for tests and timing.  Pass it with every phase of a call
-     * sequence, since the prologue and the entropy phase prepare different scratch for the two. */
+    /* Not a phase but an option, OR-ed into `phases`: rank every ranking unit with the general
+     * multi-launch selection.  By default one workgroup ranks a unit of up to 32768 tiles in a single
+     * launch, and larger units that start on 64-tile boundaries are ranked in two launches from a
+     * histogram the entropy phase builds.  Same result; meant for tests and timing.  Pass it with
+     * every phase of a call sequence, since the prologue and the entropy phase prepare different
+     * scratch for each way. */
     TAHQ_SELECT_MULTI_LAUNCH = 16
 };
 
