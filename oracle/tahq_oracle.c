@@ -227,7 +227,10 @@ static float tree_sum(float *z, uint32_t n)
  * the default configuration A = G).  Eq. 2 is printed without a minus sign, yet the text beside it says H
  * is high for evenly spread energy and low for a sharp outlier; that fixes H = -sum p log(p+varsigma)
  * (Shannon), natural log.  The norm and the entropy are sums over the A channels: inside each
- * quantization tile by the pairwise tree, and across the m tiles from left to right. */
+ * quantization tile by the pairwise tree, and across the m tiles from left to right.
+ * Order of evaluation: with r = 1/(L1 + eps) the probability is p = |v| r, and the common factor r is taken out
+ * of Eq. 2's sum: H = -r * sum |v| log(|v| r + varsigma), the argument of the logarithm being one fused
+ * multiply-add. */
 float tahq_oracle_entropy_alloc(const float *v, uint32_t G, uint32_t m, float eps_l1, float eps_log)
 {
     float w[128];
@@ -240,13 +243,13 @@ float tahq_oracle_entropy_alloc(const float *v, uint32_t G, uint32_t m, float ep
     float W = 0.0f;
     for (uint32_t q = 0; q < m; ++q) {
         for (uint32_t k = 0; k < G; ++k) {
-            float p = fabsf(v[q * G + k]) * invL;
-            float u = p + eps_log;
-            w[k] = p * tahq_oracle_log(u);
+            float a = fabsf(v[q * G + k]);
+            float u = fmaf(a, invL, eps_log);
+            w[k] = a * tahq_oracle_log(u);
         }
         W = W + tree_sum(w, G);
     }
-    return 0.0f - W;
+    return 0.0f - invL * W;
 }
 
 /* The default A = G: the allocation tile is the quantization tile. */

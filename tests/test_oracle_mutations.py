@@ -15,8 +15,9 @@ import test_oracle_pins as pins
 SRC = open(build_oracle.SRC).read()
 
 MUTATIONS = [
-    ("entropy without the Shannon minus sign", "return 0.0f - W;", "return W;"),
-    ("entropy of unnormalized magnitudes", "float p = fabsf(v[q * G + k]) * invL;", "float p = fabsf(v[q * G + k]);"),
+    ("entropy without the Shannon minus sign", "return 0.0f - invL * W;", "return invL * W;"),
+    ("entropy without the common factor 1/(L1 + eps)", "return 0.0f - invL * W;", "return 0.0f - W;"),
+    ("entropy of unnormalized magnitudes", "float u = fmaf(a, invL, eps_log);", "float u = a + eps_log;"),
     ("allocation tile normalised per quantization tile", "        L1 = L1 + tree_sum(w, G);\n    }\n    float invL = 1.0f / (L1 + eps_l1);\n    float W = 0.0f;\n    for (uint32_t q = 0; q < m; ++q) {\n",
      "        L1 = L1 + tree_sum(w, G);\n    }\n    float invL = 1.0f / (L1 + eps_l1);\n    float W = 0.0f;\n    for (uint32_t q = 0; q < m; ++q) {\n        for (uint32_t k = 0; k < G; ++k) w[k] = fabsf(v[q * G + k]);\n        invL = 1.0f / (tree_sum(w, G) + eps_l1);\n"),
     ("allocation tile entropy keeps only its last quantization tile", "W = W + tree_sum(w, G);", "W = tree_sum(w, G);"),
