@@ -203,11 +203,11 @@ struct LaunchAllocEntropy {
         }
         q(k_tile_partial<G, BF16, false>, dim3(nb), dim3(B::TILES), d_in,
                            (const float *)nullptr, part, T, m, eps_log);
-        q(k_alloc_reduce<false>, dim3(blocks_for(n_alloc)), dim3(256), (const float *)part,
+        q(k_alloc_reduce<false>, dim3(blocks_for(n_alloc)), dim3(256), (const float *)part, (const float *)nullptr,
                            inv_norm, n_alloc, m, eps_l1);
         q(k_tile_partial<G, BF16, true>, dim3(nb), dim3(B::TILES), d_in,
                            (const float *)inv_norm, part, T, m, eps_log);
-        q(k_alloc_reduce<true>, dim3(blocks_for(n_alloc)), dim3(256), (const float *)part,
+        q(k_alloc_reduce<true>, dim3(blocks_for(n_alloc)), dim3(256), (const float *)part, (const float *)inv_norm,
                            d_H, n_alloc, m, eps_l1);
     }
 };

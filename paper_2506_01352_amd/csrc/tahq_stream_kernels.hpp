@@ -153,12 +153,8 @@ __device__ __forceinline__ float entropy_of_row(const uint8_t *row, float eps_l1
     const float L1 = tree_sum<G>(a);
     const float invL = 1.0f / (L1 + eps_l1);
 #pragma unroll
-    for (int k = 0; k < G; ++k) {
-        const float p = a[k] * invL;
-        const float u = p + eps_log;
-        a[k] = p * log_contract(u);
-    }
-    return 0.0f - tree_sum<G>(a);
+    for (int k = 0; k < G; ++k) a[k] = a[k] * log_contract(__builtin_fmaf(a[k], invL, eps_log));
+    return 0.0f - invL * tree_sum<G>(a);
 }
 
 constexpr int kDigit0Bits = 10;                  // first radix digit of the selection: key bits 31..22
@@ -250,7 +246,8 @@ void k_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_t T, f
 // from left to right.  In general the work splits into two streaming passes with a small reduction after
 // each:
 //   WEIGHTED = false: part[j] = sum over tile j of |v|
-//   WEIGHTED = true:  part[j] = sum over tile j of p log(p + varsigma), p = |v| * inv_norm[j / m]
+//   WEIGHTED = true:  part[j] = sum over tile j of |v| log(|v| * r + varsigma), r = inv_norm[j / m] (the common factor r
+//                     of Eq. 2's sum is applied once, by the reduction)
 // One workgroup per batch of tiles, one lane per tile.
 template <int G, bool BF16, bool WEIGHTED>
 __global__ __launch_bounds__((Batch<G, BF16 ? 2 : 4>::TILES))
@@ -282,11 +279,7 @@ void k_tile_partial(const void *__restrict__ in, const float *__restrict__ inv_n
     if constexpr (WEIGHTED) {
         const float invL = inv_norm[j / m];
 #pragma unroll
-        for (int k = 0; k < G; ++k) {
-            const float p = a[k] * invL;
-            const float u = p + eps_log;
-            a[k] = p * log_contract(u);
-        }
+        for (int k = 0; k < G; ++k) a[k] = a[k] * log_contract(__builtin_fmaf(a[k], invL, eps_log));
     }
     part[j] = tree_sum<G>(a);
 }
@@ -336,33 +329,30 @@ void k_alloc_entropy(const void *__restrict__ in, float *__restrict__ H, uint32_
     if (valid) {
         const float invL = inv_norm[(uint32_t)tid / m];
 #pragma unroll
-        for (int k = 0; k < G; ++k) {
-            const float p = a[k] * invL;
-            const float u = p + eps_log;
-            a[k] = p * log_contract(u);
-        }
+        for (int k = 0; k < G; ++k) a[k] = a[k] * log_contract(__builtin_fmaf(a[k], invL, eps_log));
         part[tid] = tree_sum<G>(a);
     }
     __syncthreads();
     if (first) {
         float acc = 0.0f;
         for (uint32_t q = 0; q < m; ++q) acc = acc + part[tid + q];
-        H[((uint32_t)j0 + tid) / m] = 0.0f - acc;
+        H[((uint32_t)j0 + tid) / m] = 0.0f - inv_norm[(uint32_t)tid / m] * acc;
     }
 }
 
 // Left-to-right sum of the m partial sums of every allocation tile.  FINAL = false: the reciprocal norm
-// 1 / (L1 + eps) of Eq. 1; FINAL = true: the entropy 0 - sum of Eq. 2.
+// r = 1 / (L1 + eps) of Eq. 1; FINAL = true: the entropy 0 - r * sum of Eq. 2, with r read from `inv_norm`.
 template <bool FINAL>
-__global__ __launch_bounds__(256) void k_alloc_reduce(const float *__restrict__ part, float *__restrict__ out,
-                                                      uint32_t n_alloc, uint32_t m, float eps_l1)
+__global__ __launch_bounds__(256) void k_alloc_reduce(const float *__restrict__ part, const float *__restrict__ inv_norm,
+                                                      float *__restrict__ out, uint32_t n_alloc, uint32_t m, float eps_l1)
 {
     const uint32_t ja = blockIdx.x * 256 + threadIdx.x;
     if (ja >= n_alloc) return;
     const float *p = part + (uint64_t)ja * m;
     float acc = 0.0f;
     for (uint32_t q = 0; q < m; ++q) acc = acc + p[q];
-    out[ja] = FINAL ? 0.0f - acc : 1.0f / (acc + eps_l1);
+    if constexpr (FINAL) out[ja] = 0.0f - inv_norm[ja] * acc;
+    else out[ja] = 1.0f / (acc + eps_l1);
 }
 
 // ------------------------------------ K3: transform + quantize + pack
