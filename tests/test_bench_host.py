@@ -84,3 +84,16 @@ def test_stored_counter_readings_come_from_the_profile_summaries():
         per_tile, pct = valu[kernel]
         assert 300 < per_tile < 1500 and 30 < pct < 130, (kernel, per_tile, pct)
     assert bench.stored_valu("valu_counters_no_such_workload") == (None, None)
+
+
+def test_settling_steps_follow_the_requested_time():
+    # bench.py runs plain untimed steps right before the timed region for about --settle-ms at the step time the warm-up
+    # saw: at least --settle of them, at most 20000
+    sys.path.insert(0, ROOT)
+    import bench
+    from types import SimpleNamespace as NS
+    assert bench.settle_steps(NS(settle=10, settle_ms=150.0), 0.37) == int(150.0 / 0.37) + 1
+    assert bench.settle_steps(NS(settle=10, settle_ms=0.0), 0.37) == 10
+    assert bench.settle_steps(NS(settle=500, settle_ms=150.0), 0.37) == 500
+    assert bench.settle_steps(NS(settle=10, settle_ms=150.0), 0.001) == 20000
+    assert bench.settle_steps(NS(settle=10, settle_ms=150.0), 0.0) == 10
