@@ -101,7 +101,7 @@ def cpu_baseline(index, w, alloc_tile, low_bits, budget):
     """The oracle as it stands, single thread, on a bounded sample of the same workload."""
     import workloads
     from oracle import o32
-    batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
+    batch = max(1, min(w.batch, (270_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
     ws, x = workloads.generate(index, batch=batch, seq=w.seq, hidden=w.hidden)
     ocfg = o32.make_cfg(ws.batch, ws.seq, ws.hidden, w.tile, ws.dtype, budget, alloc_tile=alloc_tile, low_bits=low_bits)
     t0 = time.perf_counter()
@@ -202,7 +202,7 @@ def naive_main(args):
     }
     if not args.no_cpu_baseline:
         from oracle import n32
-        batch = max(1, min(w.batch, (150_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
+        batch = max(1, min(w.batch, (270_000_000 + w.seq * w.hidden - 1) // (w.seq * w.hidden)))
         ws, xs = workloads.generate(index, batch=batch)
         ocfg = n32.make_cfg(ws.batch, ws.seq, ws.hidden, ws.dtype, args.bits, args.scale)
         c0 = time.perf_counter()
