@@ -41,6 +41,8 @@ def test_forward_bench_line():
     assert d["ms_per_step_is"] == "wall-clock mean" and d["ms_per_step"] == d["ms_per_step_wall"]
     assert 0 < d["decode_ms"] < d["encode_ms"] < d["ms_per_step"] * 1.5
     assert d["decode_f32_out_ms"] > d["decode_ms"] and 1000 < d["copy_ceiling_gbs"] < 8000
+    assert 1000 < d["fill_ceiling_gbs"] < 8000 and d["settle_steps"] >= 10
+    assert rf["valu_instructions_per_tile"] > 100 and 0 < rf["valu_issue_utilisation_pct"] < 130
     assert 0 < d["pct_hbm_peak_algorithmic"] < d["pct_hbm_peak_of_measured_traffic"] < 100
     assert rf["traffic_source"].startswith("profiles/hbm_traffic_cfg4_")
 
